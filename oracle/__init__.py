@@ -1,0 +1,221 @@
+"""CPU oracle of the SSSD verification step -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``sssd_oracle.c`` (the arithmetic lives there, one
+plain function per operation of the paper's Table 2) plus the Python glue that
+walks the layers.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package; it shares no code
+with ``paper_2411_05894_amd`` and never imports it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from .build import LIB, build as build_oracle
+
+_lib = None
+
+
+class OrcConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("max_seq", C.c_int32)]
+
+
+class OrcLayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "mlp_norm")]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            build_oracle()
+        _lib = C.CDLL(LIB)
+        _lib.orc_bf16_to_f32.restype = C.c_float
+        _lib.orc_bf16_to_f32.argtypes = [C.c_uint16]
+        _lib.orc_f32_to_bf16.restype = C.c_uint16
+        _lib.orc_f32_to_bf16.argtypes = [C.c_float]
+        _lib.orc_argmax.restype = C.c_int32
+    return _lib
+
+
+def _p(t) -> C.c_void_p:
+    if isinstance(t, torch.Tensor):
+        assert t.device.type == "cpu" and t.is_contiguous()
+        return C.c_void_p(t.data_ptr())
+    assert t.flags["C_CONTIGUOUS"]
+    return C.c_void_p(t.ctypes.data)
+
+
+def make_config(shape, max_seq: int) -> OrcConfig:
+    return OrcConfig(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                     shape.ffn, shape.vocab, shape.rms_eps, shape.rope_base, max_seq)
+
+
+# ---- single operations (used by the pins and by kernel-level parity tests) ----
+
+def linear(x: torch.Tensor, w_bf16: torch.Tensor) -> torch.Tensor:
+    """y = x @ w^T with x fp32 [M,K], w bf16 [N,K]."""
+    x = x.contiguous().float()
+    M, K = x.shape
+    N = w_bf16.shape[0]
+    assert w_bf16.dtype == torch.bfloat16 and w_bf16.shape[1] == K
+    y = torch.empty(M, N, dtype=torch.float32)
+    lib().orc_linear(_p(x), M, K, _p(w_bf16.contiguous()), N, _p(y))
+    return y
+
+
+def rmsnorm(x: torch.Tensor, gamma_bf16: torch.Tensor, eps: float) -> torch.Tensor:
+    x = x.contiguous().float()
+    out = torch.empty_like(x)
+    rows = x.reshape(-1, x.shape[-1])
+    o = out.reshape(-1, x.shape[-1])
+    g = gamma_bf16.contiguous()
+    for r in range(rows.shape[0]):
+        lib().orc_rmsnorm(_p(rows[r]), _p(g), C.c_float(eps), rows.shape[1], _p(o[r]))
+    return out
+
+
+def rope(v: torch.Tensor, pos: int, base: float) -> torch.Tensor:
+    out = v.clone().contiguous().float()
+    lib().orc_rope(_p(out), out.numel(), int(pos), C.c_float(base))
+    return out
+
+
+def attention_row(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, n_keys: int) -> torch.Tensor:
+    """q fp32 [d]; Kc, Vc bf16 [>=n_keys, d]."""
+    d = q.numel()
+    out = torch.empty(d, dtype=torch.float32)
+    lib().orc_attention_row(_p(q.contiguous().float()), _p(Kc.contiguous()), _p(Vc.contiguous()),
+                            int(n_keys), d, _p(out))
+    return out
+
+
+def argmax(row: torch.Tensor) -> int:
+    row = row.contiguous().float()
+    return int(lib().orc_argmax(_p(row), row.numel()))
+
+
+def top2(row: torch.Tensor):
+    row = row.contiguous().float()
+    a, b = C.c_float(), C.c_float()
+    lib().orc_top2(_p(row), row.numel(), C.byref(a), C.byref(b))
+    return a.value, b.value
+
+
+def accept(tokens: Sequence[int], that: Sequence[int]):
+    k = len(tokens) - 1
+    t = np.ascontiguousarray(tokens, dtype=np.int32)
+    h = np.ascontiguousarray(that, dtype=np.int32)
+    acc, nxt = C.c_int32(), C.c_int32()
+    lib().orc_accept(_p(t), _p(h), k, C.byref(acc), C.byref(nxt))
+    return acc.value, nxt.value
+
+
+def counters_reset():
+    lib().orc_counters_reset()
+
+
+def counters():
+    a, b = C.c_double(), C.c_double()
+    lib().orc_counters_get(C.byref(a), C.byref(b))
+    return a.value, b.value
+
+
+# ---- whole model ----
+
+class OracleModel:
+    """Weights (bf16 CPU tensors) + KV cache + the layer walk.
+
+    ``layers`` is a list of dicts name -> bf16 tensor (names as in
+    ``sssd_synth.layer_weight_specs``); ``globals_`` holds embed, lm_head,
+    final_norm.  The cache is K and V, each a bf16 tensor
+    [n_layers][max_batch][n_kv_heads][max_seq][head_dim].
+    """
+
+    def __init__(self, shape, layers: List[Dict[str, torch.Tensor]], globals_: Dict[str, torch.Tensor],
+                 max_batch: int, max_seq: int):
+        self.shape = shape
+        self.cfg = make_config(shape, max_seq)
+        self.layers = layers
+        self.g = globals_
+        self.max_batch, self.max_seq = max_batch, max_seq
+        cs = (shape.n_layers, max_batch, shape.n_kv_heads, max_seq, shape.head_dim)
+        self.K = torch.zeros(cs, dtype=torch.bfloat16)
+        self.V = torch.zeros(cs, dtype=torch.bfloat16)
+
+    def _lw(self, l: int) -> OrcLayerWeights:
+        w = self.layers[l]
+        return OrcLayerWeights(*[w[n].data_ptr() for n in
+                                 ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "mlp_norm")])
+
+    def embed(self, tokens: torch.Tensor) -> torch.Tensor:
+        tok = tokens.reshape(-1).to(torch.int32).contiguous()
+        x = torch.empty(tok.numel(), self.shape.hidden, dtype=torch.float32)
+        lib().orc_embed(C.byref(self.cfg), _p(self.g["embed"]), _p(tok), tok.numel(), _p(x))
+        return x
+
+    def layer_verify(self, l: int, x: torch.Tensor, lens: torch.Tensor, B: int, k: int) -> None:
+        """Run layer ``l`` on x [B*(k+1), hidden] in place for sequences 0..B-1."""
+        lw = self._lw(l)
+        lens = lens.to(torch.int32).contiguous()
+        lib().orc_layer_verify(C.byref(self.cfg), C.byref(lw), _p(x), _p(self.K[l]), _p(self.V[l]),
+                               _p(lens), B, k)
+
+    def lm_head(self, x: torch.Tensor) -> torch.Tensor:
+        M = x.shape[0]
+        logits = torch.empty(M, self.shape.vocab, dtype=torch.float32)
+        lib().orc_lm_head(C.byref(self.cfg), _p(self.g["final_norm"]), _p(self.g["lm_head"]), _p(x), M,
+                          _p(logits))
+        return logits
+
+    def verify_step(self, tokens: torch.Tensor, lens: torch.Tensor, return_hidden: bool = False):
+        """The verify pass: tokens int [B][k+1], lens int [B] (valid cache rows
+        before the step).  Appends k+1 K/V rows per sequence and layer; does not
+        change ``lens``.  Returns dict with logits [B][k+1][V], argmax ids
+        ``that`` [B][k+1], ``accepted_len`` [B], ``next_token`` [B]."""
+        B, sq = tokens.shape
+        k = sq - 1
+        assert B <= self.max_batch and int(lens.max()) + sq <= self.max_seq
+        x = self.embed(tokens)
+        for l in range(self.shape.n_layers):
+            self.layer_verify(l, x, lens, B, k)
+        logits = self.lm_head(x).view(B, sq, -1)
+        that = torch.empty(B, sq, dtype=torch.int32)
+        acc = torch.empty(B, dtype=torch.int32)
+        nxt = torch.empty(B, dtype=torch.int32)
+        for b in range(B):
+            for j in range(sq):
+                that[b, j] = argmax(logits[b, j])
+            a, n = accept(tokens[b].tolist(), that[b].tolist())
+            acc[b], nxt[b] = a, n
+        out = {"logits": logits, "that": that, "accepted_len": acc, "next_token": nxt}
+        if return_hidden:
+            out["hidden"] = x.view(B, sq, -1)
+        return out
+
+    def decode_token(self, b: int, token: int, pos: int) -> torch.Tensor:
+        """Plain autoregressive step of sequence ``b``: logits [V] for the token at ``pos``."""
+        x = self.embed(torch.tensor([token]))
+        for l in range(self.shape.n_layers):
+            lw = self._lw(l)
+            lib().orc_layer_decode_token(C.byref(self.cfg), C.byref(lw), _p(x), _p(self.K[l, b]),
+                                         _p(self.V[l, b]), int(pos))
+        return self.lm_head(x)[0]
+
+
+def build_model(shape, seed: int, max_batch: int, max_seq: int, unit_gains: bool = True) -> OracleModel:
+    """Generate every weight of ``shape`` on the CPU with the shared seeded generator."""
+    from sssd_synth import TensorId, global_weight_specs, layer_weight_specs, make_weight
+    layers = []
+    for l in range(shape.n_layers):
+        layers.append({n: make_weight(seed, n, TensorId.layer(l, slot), shp, unit_gains=unit_gains)
+                       for n, slot, shp in layer_weight_specs(shape)})
+    g = {n: make_weight(seed, n, tid, shp, unit_gains=unit_gains) for n, tid, shp in global_weight_specs(shape)}
+    return OracleModel(shape, layers, g, max_batch, max_seq)
