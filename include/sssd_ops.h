@@ -1,0 +1,43 @@
+/*
+ * sssd_ops.h -- kernel-level entry points of libsssd_verify, for parity tests and
+ * micro-benchmarks of single operations of the verify step (the rows of the
+ * paper's Table 2, App. B).  Same conventions as sssd_verify.h: device pointers
+ * are caller-owned, calls enqueue on `stream` and return 0 or a negative SSSD_E*.
+ */
+#ifndef SSSD_OPS_H
+#define SSSD_OPS_H
+
+#include "sssd_verify.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Bytes of the tile-ordered form of a bf16 matrix [N][K] (K padded to 32; N % 16 == 0),
+ * and of one half (hi or lo) of the tile-ordered activations of M rows x K. */
+size_t sssd_op_packed_weight_bytes(int32_t N, int32_t K);
+size_t sssd_op_packed_act_bytes(int32_t M, int32_t K);
+
+/* w: device bf16 [N][K] row-major -> packed: device, sssd_op_packed_weight_bytes(N, K). */
+int sssd_op_pack_weight(const void *w, void *packed, int32_t N, int32_t K, void *stream);
+
+/* x: device fp32 [M][K] -> a_hi, a_lo: device, sssd_op_packed_act_bytes(M, K) each, which
+ * the caller zero-filled once (padding must read as zero); x ~= hi + lo, both bf16. */
+int sssd_op_pack_activation(const float *x, int32_t M, int32_t K, void *a_hi, void *a_lo, void *stream);
+
+/* Table 2 linear rows: out[M][N] (device fp32, row-major) = X[M][K] . W[N][K]^T with fp32
+ * accumulation.  a_lo == NULL uses the bf16 hi part alone. */
+int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K,
+                 float *out, void *stream);
+
+/* Table 2 attention row on a context's cache: q device fp32 [B][k+1][n_q_heads][head_dim]
+ * (already rotated), lens device int32 [B] (the k+1 new K/V rows of `layer` must already be
+ * in the cache at lens[b]..lens[b]+k, e.g. via sssd_kv_import); row j attends to cache rows
+ * 0..lens[b]+j.  out device fp32 [B][k+1][n_q_heads*head_dim].  Uses the context's scratch. */
+int sssd_op_attention(sssd_ctx *ctx, int32_t layer, int32_t B, int32_t k, const float *q, const int32_t *lens,
+                      float *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSSD_OPS_H */

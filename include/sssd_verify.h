@@ -1,0 +1,171 @@
+/*
+ * sssd_verify.h -- C ABI of the SSSD verification step on one MI355X (gfx950).
+ *
+ * The paper (SSSD, arXiv 2411.05894) drafts candidate tokens on the host and
+ * has the target model verify "the last generated token and the speculated
+ * tokens" in a single forward pass (Sec. 2; Sec. 3.2, first paragraph).  This
+ * library is that device-side step for a linear chain of k drafts per
+ * sequence: one pass of a Llama-style decoder over b sequences x s_q = k+1
+ * tokens (the operations of Table 2, App. B, with p = 1), K/V of all k+1 rows
+ * appended in place to a per-sequence cache, then greedy acceptance.
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory owned by the CALLER; the library
+ *    never allocates or frees device memory.  "host" pointers are ordinary
+ *    process memory.
+ *  - All weights are bf16 (2 bytes, Table 2 caption), matrices row-major
+ *    [out][in] (the transpose of the paper's X.W orientation, same product).
+ *  - Every function returns 0 (SSSD_OK) or a negative SSSD_E* code; nothing
+ *    is printed and nothing aborts.  sssd_strerror() names a code.
+ *  - Calls that take a `stream` only enqueue work on that hipStream_t (passed
+ *    as void*; NULL = the default stream) and return without waiting.
+ */
+#ifndef SSSD_VERIFY_H
+#define SSSD_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SSSD_OK 0
+#define SSSD_EINVAL (-1)    /* null pointer, bad handle, unsupported shape            */
+#define SSSD_ECAPACITY (-2) /* B > max_batch, k > max_k, buffer too small             */
+#define SSSD_ENOSPACE (-3)  /* some lens[b] + k + 1 > max_seq, or a token id >= vocab
+                               (found on the device, reported by sssd_verify_sync)    */
+#define SSSD_EHIP (-4)      /* a HIP runtime call failed                              */
+
+typedef struct sssd_ctx sssd_ctx; /* opaque, host memory owned by the library */
+
+/* Model and capacity.  Notation of Table 2: hidden = h, n_q_heads = n_q,
+ * n_kv_heads = n_kv, head_dim = d, ffn = h_mlp.  Supported: head_dim 64 or 128;
+ * n_q_heads a multiple of n_kv_heads; hidden, n_q*d, n_kv*d, ffn, vocab multiples of 16;
+ * max_k <= 31.  No biases, untied embedding / LM head, RMSNorm with eps inside the
+ * square root, rotary embedding pairing element i with i + d/2 at angle
+ * pos * rope_base^(-2i/d), softmax scale 1/sqrt(d), SwiGLU = silu(gate) * up. */
+typedef struct {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    float rms_eps, rope_base;
+    int32_t max_batch; /* largest B of any step                                   */
+    int32_t max_k;     /* largest number of drafts per sequence                   */
+    int32_t max_seq;   /* KV rows kept per sequence (context + k+1 must fit)      */
+} sssd_model_config;
+
+/* Device pointers to the bf16 weights.  wq..mlp_norm are HOST arrays of
+ * n_layers device pointers.  Shapes: embed, lm_head [vocab][hidden];
+ * wq [n_q*d][hidden]; wk, wv [n_kv*d][hidden]; wo [hidden][n_q*d];
+ * w_gate, w_up [ffn][hidden]; w_down [hidden][ffn]; norms [hidden]. */
+typedef struct {
+    const void *embed, *lm_head, *final_norm;
+    const void *const *wq, *const *wk, *const *wv, *const *wo;
+    const void *const *w_gate, *const *w_up, *const *w_down;
+    const void *const *attn_norm, *const *mlp_norm;
+} sssd_weights;
+
+/* Flags of sssd_verify_init. */
+#define SSSD_PACK_IN_PLACE 1u /* reorder each weight matrix inside the caller's own buffer
+                                 (needs hidden, n_q*d and ffn to be multiples of 32);
+                                 the caller's matrices are then in the library's private
+                                 tile order until the process frees them                  */
+
+/* Bytes the caller must provide for a configuration (host computation only).
+ * packed_weight_bytes is what `packed` must hold when SSSD_PACK_IN_PLACE is not
+ * used (0 bytes are needed with it).  Any out pointer may be NULL. */
+int sssd_verify_sizes(const sssd_model_config *cfg, size_t *kv_bytes, size_t *ws_bytes,
+                      size_t *packed_weight_bytes);
+
+/*
+ * Create a context.  Synchronous (it waits for its own device work):
+ *  - zero-fills kv_cache (device, >= kv_bytes) -- the cache layout is private,
+ *    use sssd_kv_import / sssd_kv_export to move rows in and out;
+ *  - reorders every weight matrix into the tile order the GEMM kernels stream,
+ *    either into `packed` (device, >= packed_weight_bytes; the caller may free
+ *    the original matrices afterwards, but not embed and the three norm
+ *    vectors, which are used where they are) or in place (SSSD_PACK_IN_PLACE,
+ *    packed may be NULL);
+ *  - lays out `workspace` (device, >= ws_bytes, 256-byte aligned).
+ * All buffers must outlive the context.  *out is written only on success.
+ */
+int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *weights, void *kv_cache,
+                     size_t kv_bytes, void *workspace, size_t ws_bytes, void *packed,
+                     size_t packed_bytes, uint32_t flags, sssd_ctx **out);
+
+/*
+ * One verification step, enqueued on `stream`.
+ *   tokens       device int32 [B][k+1]; tokens[b][0] is the last accepted token
+ *                (not yet in the cache), tokens[b][1..k] the drafts
+ *   lens         device int32 [B]; valid cache rows of sequence b BEFORE the step
+ *   accepted_len device int32 [B] out; number of drafts accepted, in 0..k: the
+ *                longest prefix with tokens[b][i+1] == argmax(logits[b][i])
+ *   next_token   device int32 [B] out; argmax(logits[b][accepted_len[b]]), the
+ *                bonus token, so accepted drafts + next_token is exactly what greedy
+ *                decoding emits.  Ties in argmax go to the lowest token id.
+ * Sequence b is cache slot b (0 <= b < B <= max_batch).  The step writes K/V
+ * rows lens[b] .. lens[b]+k of every layer and does NOT change lens; rows of
+ * rejected drafts stay behind as dead data and are overwritten by the next
+ * step (sssd_kv_rollback computes the new lens).
+ * If some lens[b] + k + 1 > max_seq or a token id is outside [0, vocab), that
+ * sequence is processed as if lens = 0 / token = 0 (all accesses stay in
+ * bounds), its outputs are meaningless, and a sticky device flag makes the
+ * next sssd_verify_sync return SSSD_ENOSPACE.
+ * Steps on the same context must be ordered (same stream, or synchronised).
+ */
+int sssd_verify_step(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
+                     const int32_t *lens, int32_t *accepted_len, int32_t *next_token,
+                     void *stream);
+
+/*
+ * Commit or roll back, enqueued on `stream`.  lens is device int32 [B], in-out.
+ *   accepted_len != NULL: lens[b] += accepted_len[b] + 1  (root + accepted drafts stay)
+ *   else new_lens != NULL: lens[b]  = new_lens[b]          (arbitrary rollback / chunked prefill)
+ * No cache data moves: rows at or beyond lens[b] are simply dead.
+ */
+int sssd_kv_rollback(sssd_ctx *ctx, int32_t B, int32_t *lens, const int32_t *accepted_len,
+                     const int32_t *new_lens, void *stream);
+
+/* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call
+ * raised the device flag (and clear it), else SSSD_OK. */
+int sssd_verify_sync(sssd_ctx *ctx, void *stream);
+
+/* Parity aid.  logits != NULL: every following step also stores its fp32
+ * logits to `logits`, device float [B*(k+1)][vocab] (row b*(k+1)+j).
+ * hidden != NULL: and the residual stream after the last layer, device float
+ * [B*(k+1)][hidden].  NULL switches a store off again. */
+int sssd_debug_outputs(sssd_ctx *ctx, float *logits, float *hidden);
+
+/*
+ * Copy cache rows in (e.g. a prefilled prompt) or out, enqueued on `stream`.
+ * src/dst are device bf16 [n_kv_heads][n_rows][head_dim] for cache slot b of
+ * `layer`, covering rows t0 .. t0+n_rows-1 (t0 + n_rows <= max_seq).
+ */
+int sssd_kv_import(sssd_ctx *ctx, int32_t layer, int32_t b, int32_t t0, int32_t n_rows,
+                   const void *k_src, const void *v_src, void *stream);
+int sssd_kv_export(sssd_ctx *ctx, int32_t layer, int32_t b, int32_t t0, int32_t n_rows,
+                   void *k_dst, void *v_dst, void *stream);
+
+/*
+ * Timing aid for benchmarks.  With profiling on, sssd_verify_step brackets its
+ * launches of each kernel class with HIP events on the step's stream (no other
+ * change to the work).  sssd_profile_read waits for the stream and returns, per
+ * class c < SSSD_PROF_CLASSES, the summed milliseconds ms[c] and launch counts
+ * n[c] since profiling was switched on (host arrays), then resets them.
+ */
+#define SSSD_PROF_CLASSES 8
+enum {
+    SSSD_PROF_GEMM = 0,  /* all weight GEMMs                   */
+    SSSD_PROF_ATTN = 1,  /* attention + its split combine      */
+    SSSD_PROF_ELEM = 2,  /* embed, norms, rope/append          */
+    SSSD_PROF_ACCEPT = 3 /* arg-max merge + prefix acceptance  */
+};
+int sssd_profile_enable(sssd_ctx *ctx, int32_t on);
+int sssd_profile_read(sssd_ctx *ctx, void *stream, double *ms, int64_t *n);
+
+int sssd_verify_destroy(sssd_ctx *ctx);
+const char *sssd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSSD_VERIFY_H */

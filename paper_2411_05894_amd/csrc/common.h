@@ -1,0 +1,64 @@
+// Shared device helpers and layout definitions of the SSSD verify library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // one 16-byte lane record
+
+#define SSSD_WAVE 64
+
+// ---- bf16 helpers (round to nearest even, finite inputs) ----
+__device__ __forceinline__ uint32_t f32_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float bits_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = f32_bits(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return bits_f32((uint32_t)b << 16); }
+// x ~= hi + lo with both parts bf16: the pair carries ~16 mantissa bits.
+__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
+{
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+
+// ---- MFMA operand tile order -------------------------------------------------
+// v_mfma_f32_16x16x32_bf16 reads, per lane l, 8 bf16 of a 16 x 32 operand tile:
+// row/column l % 16, k-slots 8*(l/16) .. 8*(l/16)+7.  A "packed" matrix stores
+// each such tile as 64 consecutive 16-byte lane records (1 KiB), tiles ordered
+// [row_tile][k_tile], so that a wave fetches a whole tile with one fully
+// coalesced 16-byte-per-lane load.  Element (r, k) of a packed matrix with KT
+// k-tiles lives at bf16 index:
+__host__ __device__ __forceinline__ size_t packed_index(int r, int k, int KT)
+{
+    return ((((size_t)(r >> 4) * KT + (k >> 5)) * 64 + (size_t)(((k & 31) >> 3) * 16 + (r & 15))) << 3) + (k & 7);
+}
+
+// ---- V cache order -------------------------------------------------------------
+// V of one (layer, sequence, kv head) is stored in blocks of 32 positions; a
+// block holds head_dim/16 operand tiles of 1 KiB.  Lane l = 16*q + c of tile dt
+// holds channel dt*16 + c at the 8 positions {4q..4q+3} u {16+4q..16+4q+3} of the
+// block: exactly the positions whose scores that lane owns after the two
+// 16-position score MFMAs, so probabilities feed the second MFMA without any
+// cross-lane movement.  bf16 index of (t, ch) within the (layer, b, head) slab:
+__host__ __device__ __forceinline__ size_t vcache_index(int t, int ch, int head_dim)
+{
+    int tb = t >> 5, tt = t & 31;
+    int q = (tt & 15) >> 2, e = (tt & 3) + ((tt >> 4) << 2);
+    return ((((size_t)tb * (head_dim >> 4) + (ch >> 4)) * 64 + (size_t)(q * 16 + (ch & 15))) << 3) + e;
+}
+
+// Model dimensions and buffer map handed to every kernel launcher.
+struct Dims {
+    int L, h, nq, nkv, d, f, V;
+    int qd, kd, g;       // nq*d, nkv*d, nq/nkv
+    int max_batch, max_k, max_seq, seq_pad;  // seq_pad = max_seq rounded up to 32
+    int chunk, max_splits;                   // attention: positions per wave, waves per (b, head)
+    float eps, rope_base;
+};
+
+__host__ __device__ __forceinline__ int round_up(int x, int m) { return (x + m - 1) / m * m; }

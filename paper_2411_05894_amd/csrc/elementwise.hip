@@ -1,0 +1,287 @@
+// Small bandwidth-trivial kernels around the GEMMs: token/length validation and
+// embedding gather, RMSNorm to packed bf16 operands, rotary embedding with
+// in-place KV append, arg-max merge + greedy prefix acceptance, rollback and
+// cache import/export.  None of them is in the paper's Table 2 (it lists the
+// matrix operations only); they move O(M*h) bytes against O(params) for the GEMMs.
+#include "kernels.h"
+
+namespace {
+
+__device__ __forceinline__ float block_sum(float v, float *sh)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int w = 0; w < nw; ++w) t += sh[w];
+    __syncthreads();
+    return t;
+}
+
+// grid = M rows.  Row m = b*(k+1)+j.  The j == 0 block of each sequence validates lens[b].
+__global__ __launch_bounds__(256) void embed_kernel(Dims D, StepIO io, const uint16_t *embed, float *X,
+                                                    int32_t *pos_base, int32_t *err_flag)
+{
+    const int m = blockIdx.x, b = m / (io.k + 1), j = m % (io.k + 1);
+    int tok = io.tokens[m];
+    if (tok < 0 || tok >= D.V) {
+        if (threadIdx.x == 0) *err_flag = 1;
+        tok = 0;
+    }
+    if (j == 0 && threadIdx.x == 0) {
+        int len = io.lens[b];
+        if (len < 0 || len + io.k + 1 > D.max_seq) {
+            *err_flag = 1;
+            len = 0;
+        }
+        pos_base[b] = len;
+    }
+    const uint16_t *row = embed + (size_t)tok * D.h;
+    for (int i = threadIdx.x; i < D.h; i += blockDim.x) X[(size_t)m * D.h + i] = bf16_to_f32(row[i]);
+}
+
+// grid = M rows, 256 threads.  a = x * rsqrt(mean(x^2) + eps) * gamma -> packed bf16 hi/lo.
+__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *X, const uint16_t *gamma, int h, int KT,
+                                                           float eps, uint16_t *A_hi, uint16_t *A_lo)
+{
+    __shared__ float sh[4];
+    const int m = blockIdx.x;
+    const float *x = X + (size_t)m * h;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < h; i += blockDim.x) ss += x[i] * x[i];
+    ss = block_sum(ss, sh);
+    const float r = rsqrtf(ss / (float)h + eps);
+    for (int i = threadIdx.x; i < h; i += blockDim.x) {
+        const float a = x[i] * r * bf16_to_f32(gamma[i]);
+        uint16_t hi, lo;
+        split_bf16(a, hi, lo);
+        const size_t idx = packed_index(m, i, KT);
+        A_hi[idx] = hi;
+        A_lo[idx] = lo;
+    }
+}
+
+// grid = (M, nq + 2*nkv) ; block = d/2 threads.  One (row, head) per block.
+// qkv row layout: [nq*d | nkv*d | nkv*d] fp32.  rope_cs: [max_seq][d/2][2] (cos, sin).
+__global__ void rope_append_kernel(Dims D, const float *qkv, const int32_t *pos_base, int k, const float *rope_cs,
+                                   uint16_t *Qp, uint16_t *Kc, uint16_t *Vc, int q_rows_pad)
+{
+    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
+    const int b = m / (k + 1), j = m % (k + 1);
+    const int pos = pos_base[b] + j;
+    const int half = D.d >> 1;
+    const float *src = qkv + (size_t)m * (D.qd + 2 * D.kd) + (size_t)head * D.d;
+    const float x0 = src[i], x1 = src[i + half];
+    const size_t slab = ((size_t)b * D.nkv) * D.seq_pad * D.d;  // + kvh * seq_pad * d
+    if (head < D.nq + D.nkv) {
+        const float c = rope_cs[((size_t)pos * half + i) * 2], s = rope_cs[((size_t)pos * half + i) * 2 + 1];
+        const float y0 = x0 * c - x1 * s, y1 = x0 * s + x1 * c;
+        if (head < D.nq) {
+            const int kvh = head / D.g, hl = head % D.g;
+            const int r = j * D.g + hl;
+            uint16_t *q = Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d;
+            q[packed_index(r, i, D.d >> 5)] = f32_to_bf16(y0);
+            q[packed_index(r, i + half, D.d >> 5)] = f32_to_bf16(y1);
+        } else {
+            const int kvh = head - D.nq;
+            uint16_t *kr = Kc + slab + ((size_t)kvh * D.seq_pad + pos) * D.d;
+            kr[i] = f32_to_bf16(y0);
+            kr[i + half] = f32_to_bf16(y1);
+        }
+    } else {
+        const int kvh = head - D.nq - D.nkv;
+        uint16_t *v = Vc + slab + (size_t)kvh * D.seq_pad * D.d;
+        v[vcache_index(pos, i, D.d)] = f32_to_bf16(x0);
+        v[vcache_index(pos, i + half, D.d)] = f32_to_bf16(x1);
+    }
+}
+
+// grid = B, block = 256.  Row arg-max from the LM head's per-tile partials (lowest id
+// wins ties), then the longest draft prefix the arg-max chain reproduces.
+__global__ __launch_bounds__(256) void accept_kernel(StepIO io, const float *part_val, const int *part_idx, int NT,
+                                                     int32_t *that_dbg)
+{
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    __shared__ int that[32];
+    const int b = blockIdx.x, sq = io.k + 1;
+    for (int j = 0; j < sq; ++j) {
+        const size_t row = (size_t)(b * sq + j) * NT;
+        float bv = -INFINITY;
+        int bi = 0x7FFFFFFF;
+        for (int t = threadIdx.x; t < NT; t += blockDim.x) {
+            const float v = part_val[row + t];
+            const int id = part_idx[row + t];
+            if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 4; ++w)
+                if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+            that[j] = bi;
+            if (that_dbg) that_dbg[b * sq + j] = bi;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        int n = 0;
+        while (n < io.k && io.tokens[b * sq + n + 1] == that[n]) ++n;
+        io.accepted_len[b] = n;
+        io.next_token[b] = that[n];
+    }
+}
+
+__global__ void rollback_kernel(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    if (accepted_len) lens[b] += accepted_len[b] + 1;
+    else lens[b] = new_lens[b];
+}
+
+// grid = (n_rows, nkv), block = d.  ext layout [nkv][n_rows][d].
+__global__ void kv_copy_kernel(Dims D, uint16_t *Kc, uint16_t *Vc, int t0, int n_rows, uint16_t *k_ext, uint16_t *v_ext,
+                               bool import)
+{
+    const int t = blockIdx.x, kvh = blockIdx.y, i = threadIdx.x;
+    uint16_t *kc = Kc + ((size_t)kvh * D.seq_pad + t0 + t) * D.d + i;
+    uint16_t *vc = Vc + (size_t)kvh * D.seq_pad * D.d + vcache_index(t0 + t, i, D.d);
+    const size_t e = ((size_t)kvh * n_rows + t) * D.d + i;
+    if (import) {
+        *kc = k_ext[e];
+        *vc = v_ext[e];
+    } else {
+        k_ext[e] = *kc;
+        v_ext[e] = *vc;
+    }
+}
+
+
+// grid = M rows.  Plain fp32 -> packed bf16 hi/lo (no normalisation).
+__global__ __launch_bounds__(256) void pack_act_kernel(const float *X, int K, int KT, uint16_t *A_hi, uint16_t *A_lo)
+{
+    const int m = blockIdx.x;
+    for (int i = threadIdx.x; i < K; i += blockDim.x) {
+        uint16_t hi, lo;
+        split_bf16(X[(size_t)m * K + i], hi, lo);
+        const size_t idx = packed_index(m, i, KT);
+        A_hi[idx] = hi;
+        A_lo[idx] = lo;
+    }
+}
+
+// grid = M rows.  packed hi + lo -> fp32 [M][K].
+__global__ __launch_bounds__(256) void unpack_act_kernel(const uint16_t *A_hi, const uint16_t *A_lo, int K, int KT, float *X)
+{
+    const int m = blockIdx.x;
+    for (int i = threadIdx.x; i < K; i += blockDim.x) {
+        const size_t idx = packed_index(m, i, KT);
+        X[(size_t)m * K + i] = bf16_to_f32(A_hi[idx]) + bf16_to_f32(A_lo[idx]);
+    }
+}
+
+// grid = (M, nq), block = d.  Already-rotated fp32 queries -> packed Q operand buffer.
+__global__ void q_pack_kernel(Dims D, const float *q, int k, uint16_t *Qp, int q_rows_pad)
+{
+    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
+    const int b = m / (k + 1), j = m % (k + 1);
+    const int kvh = head / D.g, hl = head % D.g, r = j * D.g + hl;
+    uint16_t *dst = Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d;
+    dst[packed_index(r, i, D.d >> 5)] = f32_to_bf16(q[((size_t)m * D.nq + head) * D.d + i]);
+}
+
+__global__ void lens_kernel(Dims D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int len = lens[b];
+    if (len < 0 || len + k + 1 > D.max_seq) {
+        *err_flag = 1;
+        len = 0;
+    }
+    pos_base[b] = len;
+}
+
+}  // namespace
+
+hipError_t launch_embed(const Dims &D, const StepIO &io, const uint16_t *embed, float *X, int32_t *pos_base,
+                        int32_t *err_flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(embed_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, D, io, embed, X, pos_base, err_flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_pack(const Dims &D, const float *X, const uint16_t *gamma, int M, uint16_t *A_hi,
+                               uint16_t *A_lo, hipStream_t s)
+{
+    hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(M), dim3(256), 0, s, X, gamma, D.h, (D.h + 31) / 32, D.eps, A_hi, A_lo);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *pos_base, int B, int k,
+                              const float *rope_cs, uint16_t *Qp, uint16_t *Kc_layer, uint16_t *Vc_layer,
+                              hipStream_t s)
+{
+    const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
+    hipLaunchKernelGGL(rope_append_kernel, dim3(B * (k + 1), D.nq + 2 * D.nkv), dim3(D.d / 2), 0, s, D, qkv, pos_base, k,
+                       rope_cs, Qp, Kc_layer, Vc_layer, q_rows_pad);
+    return hipGetLastError();
+}
+
+hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
+                         int32_t *that_dbg, hipStream_t s)
+{
+    (void)D;
+    hipLaunchKernelGGL(accept_kernel, dim3(io.B), dim3(256), 0, s, io, part_val, part_idx, NT, that_dbg);
+    return hipGetLastError();
+}
+
+hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens, hipStream_t s)
+{
+    hipLaunchKernelGGL(rollback_kernel, dim3((B + 63) / 64), dim3(64), 0, s, B, lens, accepted_len, new_lens);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, int t0, int n_rows, uint16_t *k_ext,
+                          uint16_t *v_ext, bool import, hipStream_t s)
+{
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(kv_copy_kernel, dim3(n_rows, D.nkv), dim3(D.d), 0, s, D, Kc_slab, Vc_slab, t0, n_rows, k_ext, v_ext,
+                       import);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_act(const float *X, int M, int K, uint16_t *A_hi, uint16_t *A_lo, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_act_kernel, dim3(M), dim3(256), 0, s, X, K, (K + 31) / 32, A_hi, A_lo);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_act(const uint16_t *A_hi, const uint16_t *A_lo, int M, int K, float *X, hipStream_t s)
+{
+    hipLaunchKernelGGL(unpack_act_kernel, dim3(M), dim3(256), 0, s, A_hi, A_lo, K, (K + 31) / 32, X);
+    return hipGetLastError();
+}
+
+hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, hipStream_t s)
+{
+    const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
+    hipLaunchKernelGGL(q_pack_kernel, dim3(B * (k + 1), D.nq), dim3(D.d), 0, s, D, q, k, Qp, q_rows_pad);
+    return hipGetLastError();
+}
+
+hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag,
+                       hipStream_t s)
+{
+    hipLaunchKernelGGL(lens_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, pos_base, err_flag);
+    return hipGetLastError();
+}

@@ -1,0 +1,76 @@
+// Private launcher interface between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+#include "common.h"
+
+// ---------------------------------------------------------------- GEMM ----
+enum GemmEpilogue {
+    EPI_STORE = 0,   // out_f32[m*ld + n] = acc
+    EPI_RESID = 1,   // out_f32[m*ld + n] += acc                      (O and down projections)
+    EPI_SWIGLU = 2,  // packed bf16 hi/lo of silu(acc(W0)) * acc(W1)  (gate/up projections)
+    EPI_LMHEAD = 3   // per-(row, n-tile) arg-max partial, optional fp32 logits store
+};
+
+struct GemmArgs {
+    const u32x4 *A_hi, *A_lo;  // packed activations [m_tile][k_tile][64 lanes] (lo may be null if !split)
+    const u32x4 *W0, *W1;      // packed weights [n_tile][k_tile][64 lanes]; W1 only for EPI_SWIGLU
+    int KT;                    // k tiles of 32
+    int NT;                    // n tiles of 16 (= grid size)
+    int M;                     // valid rows; rows beyond are computed and dropped
+    float *out_f32;
+    int ld;
+    uint16_t *out_hi, *out_lo; // EPI_SWIGLU destination (packed, KT_out k-tiles)
+    int KT_out;
+    float *logits;             // EPI_LMHEAD: optional [M][ld] store (ld = vocab)
+    float *part_val;           // EPI_LMHEAD: [M][NT]
+    int *part_idx;
+};
+
+// Runs the skinny GEMM for any M (internally in passes of at most 160 rows).
+hipError_t launch_gemm(const GemmArgs &a, int epilogue, bool split, hipStream_t s);
+
+// Reorder a row-major bf16 matrix [N][K] into packed tiles (K padded to 32 with zeros).
+hipError_t launch_pack_weight(const uint16_t *src, uint16_t *dst, int N, int K, hipStream_t s);
+
+// ---------------------------------------------------------- elementwise ----
+struct StepIO {
+    const int32_t *tokens, *lens;
+    int32_t *accepted_len, *next_token;
+    int B, k;
+};
+
+// Validates lens/tokens (sticky flag, safe substitutes) and gathers embedding rows.
+hipError_t launch_embed(const Dims &D, const StepIO &io, const uint16_t *embed, float *X, int32_t *pos_base,
+                        int32_t *err_flag, hipStream_t s);
+// fp32 rows -> RMS-normalised packed bf16 hi/lo activations (K = h).
+hipError_t launch_rmsnorm_pack(const Dims &D, const float *X, const uint16_t *gamma, int M, uint16_t *A_hi,
+                               uint16_t *A_lo, hipStream_t s);
+// Rotary embedding of Q and K_new, Q to its packed operand buffer, K/V rows into the cache.
+hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *pos_base, int B, int k,
+                              const float *rope_cs, uint16_t *Qp, uint16_t *Kc_layer, uint16_t *Vc_layer,
+                              hipStream_t s);
+// Merge per-tile arg-max partials, then greedy prefix acceptance.
+hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
+                         int32_t *that_dbg, hipStream_t s);
+hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens,
+                           hipStream_t s);
+hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, int t0, int n_rows,
+                          uint16_t *k_ext, uint16_t *v_ext, bool import, hipStream_t s);
+
+// Kernel-level entry points only (parity tests, micro-benchmarks).
+hipError_t launch_pack_act(const float *X, int M, int K, uint16_t *A_hi, uint16_t *A_lo, hipStream_t s);
+hipError_t launch_unpack_act(const uint16_t *A_hi, const uint16_t *A_lo, int M, int K, float *X, hipStream_t s);
+hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, hipStream_t s);
+hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag,
+                       hipStream_t s);
+
+// ------------------------------------------------------------ attention ----
+struct AttnArgs {
+    const uint16_t *Qp;        // packed Q, one slab of q_rows_pad x d per (b, kv head)
+    const uint16_t *Kc, *Vc;   // this layer's cache
+    const int32_t *pos_base;   // validated lens
+    float *part_o;             // [b][kv head][split][q_rows_pad][d]
+    float *part_ml;            // [b][kv head][split][q_rows_pad][2]  (running max in log2 units, sum)
+    uint16_t *out_hi, *out_lo; // packed activations for the O projection (K = nq*d)
+    int B, k;
+};
+hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s);
