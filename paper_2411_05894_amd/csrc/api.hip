@@ -19,7 +19,7 @@ struct LayerW {
 struct Buffers {
     float *X, *qkv;
     uint16_t *Ah_hi, *Ah_lo, *Aq_hi, *Aq_lo, *Af_hi, *Af_lo;
-    uint16_t *Qp;
+    uint16_t *Qp, *Qp_lo;
     float *part_o, *part_ml, *part_val;
     int *part_idx;
     int32_t *pos_base, *err_flag, *that_dbg;
@@ -122,6 +122,7 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.Af_hi = (uint16_t *)take(S.tiles_alloc * KTf * 1024);
     b.Af_lo = (uint16_t *)take(S.tiles_alloc * KTf * 1024);
     b.Qp = (uint16_t *)take((size_t)D.max_batch * D.nkv * S.q_rows_pad * D.d * 2);
+    b.Qp_lo = (uint16_t *)take((size_t)D.max_batch * D.nkv * S.q_rows_pad * D.d * 2);
     const size_t prow = (size_t)D.max_batch * D.nkv * D.max_splits * S.q_rows_pad;
     b.part_o = (float *)take(prow * D.d * 4);
     b.part_ml = (float *)take(prow * 2 * 4);
@@ -376,7 +377,9 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
     hipStream_t s = (hipStream_t)stream;
     Buffers &W = c->W;
     const int M = B * (k + 1);
-    const bool split = (M + 15) / 16 <= 4;  // hi+lo activations while the GEMMs are far from the MFMA roof
+    // hi+lo activations: errors of single-bf16 activations are amplified ~30x through 32 layers
+    // of the benchmark's random-weight models and would miss the 2e-2 logit tolerance.
+    const bool split = true;
     StepIO io{tokens, lens, accepted_len, next_token, B, k};
 
     auto gemm = [&](const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W0, const uint16_t *W1, int N, int K,
@@ -408,10 +411,10 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         uint16_t *Kl = c->Kc + (size_t)l * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)l * c->S.kv_layer_elems;
         {
             Prof p(c, s, SSSD_PROF_ELEM);
-            HIP_TRY(launch_rope_append(D, W.qkv, W.pos_base, B, k, W.rope_cs, W.Qp, Kl, Vl, s));
+            HIP_TRY(launch_rope_append(D, W.qkv, W.pos_base, B, k, W.rope_cs, W.Qp, W.Qp_lo, Kl, Vl, s));
         }
         {
-            AttnArgs a{W.Qp, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
+            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
             Prof p(c, s, SSSD_PROF_ATTN);
             HIP_TRY(launch_attention(D, a, s));
         }
@@ -560,9 +563,9 @@ int sssd_op_attention(sssd_ctx *c, int32_t layer, int32_t B, int32_t k, const fl
     hipStream_t s = (hipStream_t)stream;
     Buffers &W = c->W;
     HIP_TRY(launch_lens(D, B, k, lens, W.pos_base, W.err_flag, s));
-    HIP_TRY(launch_q_pack(D, q, B, k, W.Qp, s));
+    HIP_TRY(launch_q_pack(D, q, B, k, W.Qp, W.Qp_lo, s));
     uint16_t *Kl = c->Kc + (size_t)layer * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)layer * c->S.kv_layer_elems;
-    AttnArgs a{W.Qp, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
+    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
     HIP_TRY(launch_attention(D, a, s));
     HIP_TRY(launch_unpack_act(W.Aq_hi, W.Aq_lo, B * (k + 1), D.qd, out, s));
     return SSSD_OK;

@@ -43,13 +43,17 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, in
     const uint16_t *Kc = a.Kc + slab;
     const u32x4 *Vc = reinterpret_cast<const u32x4 *>(a.Vc + slab);
     const u32x4 *Qs = reinterpret_cast<const u32x4 *>(a.Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD);
+    const u32x4 *Ql = reinterpret_cast<const u32x4 *>(a.Qp_lo + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD);
 
-    u32x4 qreg[RT][KS];
+    // q ~= hi + lo (two bf16), so the scores carry fp32-level accuracy although K is bf16.
+    u32x4 qreg[RT][KS], qlo[RT][KS];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
+        for (int ks = 0; ks < KS; ++ks) {
             qreg[rt][ks] = Qs[((size_t)(rt_base + rt) * KS + ks) * 64 + lane];
+            qlo[rt][ks] = Ql[((size_t)(rt_base + rt) * KS + ks) * 64 + lane];
+        }
 
     f32x4 o[RT][DT];
     float m_run[RT], l_run[RT];
@@ -77,7 +81,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, in
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) vreg[dt] = Vc[((size_t)(t0 >> 5) * DT + dt) * 64 + lane];
 
-        u32x4 pb[RT];
+        u32x4 pb[RT], pl[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             f32x4 s[2];
@@ -85,7 +89,10 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, in
             for (int u = 0; u < 2; ++u) {
                 s[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) s[u] = mfma(kreg[u][ks], qreg[rt][ks], s[u]);
+                for (int ks = 0; ks < KS; ++ks) {
+                    s[u] = mfma(kreg[u][ks], qreg[rt][ks], s[u]);
+                    s[u] = mfma(kreg[u][ks], qlo[rt][ks], s[u]);
+                }
             }
             // s[u][r] is the score of position t0 + 16u + 4q + r for query row rt*16 + c.
             float v[8];
@@ -106,17 +113,20 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, in
             const float alpha = exp2f(m_run[rt] - m_new);
             m_run[rt] = m_new;
             float psum = 0.f;
-            uint32_t pk[4];
+            uint32_t pk[4], pkl[4];
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
                 const float p0 = exp2f(v[e] - m_new), p1 = exp2f(v[e + 1] - m_new);
-                const uint16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
-                // the denominator sums the rounded probabilities the numerator uses
-                psum += bf16_to_f32(b0) + bf16_to_f32(b1);
-                pk[e >> 1] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+                uint16_t h0, l0, h1, l1;   // p ~= hi + lo: the probabilities keep ~16 mantissa bits
+                split_bf16(p0, h0, l0);
+                split_bf16(p1, h1, l1);
+                psum += p0 + p1;
+                pk[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                pkl[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
             }
             l_run[rt] = l_run[rt] * alpha + psum;
             pb[rt] = u32x4{pk[0], pk[1], pk[2], pk[3]};
+            pl[rt] = u32x4{pkl[0], pkl[1], pkl[2], pkl[3]};
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 o[rt][dt] *= alpha;
@@ -125,8 +135,10 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, in
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
+            for (int rt = 0; rt < RT; ++rt) {
                 o[rt][dt] = mfma(vreg[dt], pb[rt], o[rt][dt]);
+                o[rt][dt] = mfma(vreg[dt], pl[rt], o[rt][dt]);
+            }
     }
 
     // o[rt][dt][r] of lane (q, c): channel dt*16 + 4q + r of query row rt*16 + c.

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *X, const
 // grid = (M, nq + 2*nkv) ; block = d/2 threads.  One (row, head) per block.
 // qkv row layout: [nq*d | nkv*d | nkv*d] fp32.  rope_cs: [max_seq][d/2][2] (cos, sin).
 __global__ void rope_append_kernel(Dims D, const float *qkv, const int32_t *pos_base, int k, const float *rope_cs,
-                                   uint16_t *Qp, uint16_t *Kc, uint16_t *Vc, int q_rows_pad)
+                                   uint16_t *Qp, uint16_t *Qp_lo, uint16_t *Kc, uint16_t *Vc, int q_rows_pad)
 {
     const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
     const int b = m / (k + 1), j = m % (k + 1);
@@ -81,9 +81,13 @@ __global__ void rope_append_kernel(Dims D, const float *qkv, const int32_t *pos_
         if (head < D.nq) {
             const int kvh = head / D.g, hl = head % D.g;
             const int r = j * D.g + hl;
-            uint16_t *q = Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d;
-            q[packed_index(r, i, D.d >> 5)] = f32_to_bf16(y0);
-            q[packed_index(r, i + half, D.d >> 5)] = f32_to_bf16(y1);
+            const size_t qs = ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d;
+            uint16_t h0, l0, h1, l1;
+            split_bf16(y0, h0, l0);
+            split_bf16(y1, h1, l1);
+            const size_t i0 = qs + packed_index(r, i, D.d >> 5), i1 = qs + packed_index(r, i + half, D.d >> 5);
+            Qp[i0] = h0; Qp_lo[i0] = l0;
+            Qp[i1] = h1; Qp_lo[i1] = l1;
         } else {
             const int kvh = head - D.nq;
             uint16_t *kr = Kc + slab + ((size_t)kvh * D.seq_pad + pos) * D.d;
@@ -190,13 +194,16 @@ __global__ __launch_bounds__(256) void unpack_act_kernel(const uint16_t *A_hi, c
 }
 
 // grid = (M, nq), block = d.  Already-rotated fp32 queries -> packed Q operand buffer.
-__global__ void q_pack_kernel(Dims D, const float *q, int k, uint16_t *Qp, int q_rows_pad)
+__global__ void q_pack_kernel(Dims D, const float *q, int k, uint16_t *Qp, uint16_t *Qp_lo, int q_rows_pad)
 {
     const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
     const int b = m / (k + 1), j = m % (k + 1);
     const int kvh = head / D.g, hl = head % D.g, r = j * D.g + hl;
-    uint16_t *dst = Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d;
-    dst[packed_index(r, i, D.d >> 5)] = f32_to_bf16(q[((size_t)m * D.nq + head) * D.d + i]);
+    const size_t idx = ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d + packed_index(r, i, D.d >> 5);
+    uint16_t hi, lo;
+    split_bf16(q[((size_t)m * D.nq + head) * D.d + i], hi, lo);
+    Qp[idx] = hi;
+    Qp_lo[idx] = lo;
 }
 
 __global__ void lens_kernel(Dims D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag)
@@ -228,12 +235,12 @@ hipError_t launch_rmsnorm_pack(const Dims &D, const float *X, const uint16_t *ga
 }
 
 hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *pos_base, int B, int k,
-                              const float *rope_cs, uint16_t *Qp, uint16_t *Kc_layer, uint16_t *Vc_layer,
+                              const float *rope_cs, uint16_t *Qp, uint16_t *Qp_lo, uint16_t *Kc_layer, uint16_t *Vc_layer,
                               hipStream_t s)
 {
     const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
     hipLaunchKernelGGL(rope_append_kernel, dim3(B * (k + 1), D.nq + 2 * D.nkv), dim3(D.d / 2), 0, s, D, qkv, pos_base, k,
-                       rope_cs, Qp, Kc_layer, Vc_layer, q_rows_pad);
+                       rope_cs, Qp, Qp_lo, Kc_layer, Vc_layer, q_rows_pad);
     return hipGetLastError();
 }
 
@@ -272,10 +279,10 @@ hipError_t launch_unpack_act(const uint16_t *A_hi, const uint16_t *A_lo, int M, 
     return hipGetLastError();
 }
 
-hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, hipStream_t s)
+hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, uint16_t *Qp_lo, hipStream_t s)
 {
     const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
-    hipLaunchKernelGGL(q_pack_kernel, dim3(B * (k + 1), D.nq), dim3(D.d), 0, s, D, q, k, Qp, q_rows_pad);
+    hipLaunchKernelGGL(q_pack_kernel, dim3(B * (k + 1), D.nq), dim3(D.d), 0, s, D, q, k, Qp, Qp_lo, q_rows_pad);
     return hipGetLastError();
 }
 

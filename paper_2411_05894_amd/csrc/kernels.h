@@ -46,7 +46,7 @@ hipError_t launch_rmsnorm_pack(const Dims &D, const float *X, const uint16_t *ga
                                uint16_t *A_lo, hipStream_t s);
 // Rotary embedding of Q and K_new, Q to its packed operand buffer, K/V rows into the cache.
 hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *pos_base, int B, int k,
-                              const float *rope_cs, uint16_t *Qp, uint16_t *Kc_layer, uint16_t *Vc_layer,
+                              const float *rope_cs, uint16_t *Qp, uint16_t *Qp_lo, uint16_t *Kc_layer, uint16_t *Vc_layer,
                               hipStream_t s);
 // Merge per-tile arg-max partials, then greedy prefix acceptance.
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
@@ -59,13 +59,14 @@ hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, i
 // Kernel-level entry points only (parity tests, micro-benchmarks).
 hipError_t launch_pack_act(const float *X, int M, int K, uint16_t *A_hi, uint16_t *A_lo, hipStream_t s);
 hipError_t launch_unpack_act(const uint16_t *A_hi, const uint16_t *A_lo, int M, int K, float *X, hipStream_t s);
-hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, hipStream_t s);
+hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, uint16_t *Qp_lo, hipStream_t s);
 hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag,
                        hipStream_t s);
 
 // ------------------------------------------------------------ attention ----
 struct AttnArgs {
-    const uint16_t *Qp;        // packed Q, one slab of q_rows_pad x d per (b, kv head)
+    const uint16_t *Qp;        // packed Q (bf16 hi part), one slab of q_rows_pad x d per (b, kv head)
+    const uint16_t *Qp_lo;     // bf16 lo part: q ~= hi + lo
     const uint16_t *Kc, *Vc;   // this layer's cache
     const int32_t *pos_base;   // validated lens
     float *part_o;             // [b][kv head][split][q_rows_pad][d]

@@ -98,8 +98,8 @@ def test_attention_vs_oracle(shape_name, B, k, ctxs):
                 ref = oracle.attention_row(qc[b, j, hq], Ks[b][hq // g_], Vs[b][hq // g_], ctxs[b] + j + 1)
                 worst = max(worst, (ref - out[b, j, hq]).abs().max().item())
     say("  worst abs err", worst)
-    # q and the probabilities are rounded to bf16 (2^-9 relative each); outputs are O(1) or less
-    assert worst <= 8e-3
+    # q and the probabilities enter the MFMAs as bf16 hi+lo pairs (~2^-17 relative); outputs are O(1)
+    assert worst <= 1e-4
     # round trip of the cache through its private layout
     Kb = torch.empty_like(Ks[0], device=DEV); Vb = torch.empty_like(Vs[0], device=DEV)
     ctx.sssd_kv_export(0, 0, 0, Kb, Vb)
