@@ -11,10 +11,7 @@ namespace {
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
-struct LayerW {
-    const uint16_t *wq, *wk, *wv, *wo, *wg, *wu, *wd;  // packed
-    const uint16_t *attn_norm, *mlp_norm;              // as given
-};
+typedef LayerPtrs LayerW;
 
 struct Buffers {
     float *X, *qkv;
@@ -23,7 +20,12 @@ struct Buffers {
     float *part_o, *part_ml, *part_val;
     int *part_idx;
     int32_t *pos_base, *err_flag, *that_dbg;
-    float *rope_cs;
+    float *rope_cs, *ssq;
+    unsigned *bar;
+    LayerPtrs *layer_tab;
+    unsigned long long *tstamps;
+    uint16_t *mega_A[4];
+    size_t mega_stride[4], mega_half[4];
     uint8_t *staging;
     size_t staging_bytes;
 };
@@ -55,7 +57,9 @@ struct sssd_ctx {
     size_t prof_used;
     double prof_ms[SSSD_PROF_CLASSES];
     int64_t prof_n[SSSD_PROF_CLASSES];
-    int device;
+    int device, n_cu;
+    int mode;       // SSSD_MODE_*
+    bool coop_ok;
 };
 
 namespace {
@@ -130,6 +134,20 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.part_idx = (int *)take((size_t)S.m_alloc * NTv * 4);
     b.pos_base = (int32_t *)take((size_t)D.max_batch * 4);
     b.err_flag = (int32_t *)take(4);
+    b.bar = (unsigned *)take(8);
+    b.ssq = (float *)take((size_t)(2 * D.L + 1) * 48 * (D.h / 16) * 4);
+    {
+        // versioned operand buffers of the persistent kernel: 3 row tiles, one copy per (layer, role)
+        const size_t kt[4] = {KTh, KTq, KTh, KTf};
+        const size_t versions[4] = {(size_t)D.L + 1, (size_t)D.L, (size_t)D.L, (size_t)D.L};
+        for (int i = 0; i < 4; ++i) {
+            b.mega_half[i] = 3 * kt[i] * 512;
+            b.mega_stride[i] = 2 * b.mega_half[i];
+            b.mega_A[i] = (uint16_t *)take(versions[i] * b.mega_stride[i] * 2);
+        }
+    }
+    b.layer_tab = (LayerPtrs *)take((size_t)D.L * sizeof(LayerPtrs));
+    b.tstamps = (unsigned long long *)take((size_t)(4 + 6 * D.L) * 2 * 8 + 256 * 8);
     b.that_dbg = (int32_t *)take((size_t)S.m_alloc * 4);
     b.rope_cs = (float *)take((size_t)D.max_seq * (D.d / 2) * 2 * 4);
     b.staging_bytes = (size_t)64 << 20;
@@ -224,6 +242,7 @@ const char *sssd_strerror(int code)
     case SSSD_ECAPACITY: return "capacity exceeded (batch, draft count or buffer size)";
     case SSSD_ENOSPACE: return "a sequence does not fit its KV rows, or a token id is out of range";
     case SSSD_EHIP: return "HIP runtime error";
+    case SSSD_ETIMEOUT: return "a grid-wide wait inside the step kernel gave up; the step's outputs are invalid";
     default: return "unknown error";
     }
 }
@@ -341,6 +360,14 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
         lw.mlp_norm = (const uint16_t *)w->mlp_norm[l];
     }
     INIT_RC(place(w->lm_head, D.V, D.h, &c->lm_head));
+    INIT_TRY(hipMemcpyAsync(c->W.layer_tab, c->layers.data(), (size_t)D.L * sizeof(LayerPtrs), hipMemcpyHostToDevice, s));
+    {
+        hipDeviceProp_t prop;
+        INIT_TRY(hipGetDeviceProperties(&prop, c->device));
+        c->n_cu = prop.multiProcessorCount;
+        c->coop_ok = prop.cooperativeLaunch != 0;
+        c->mode = SSSD_MODE_AUTO;
+    }
     INIT_TRY(hipStreamSynchronize(s));
     c->magic = MAGIC;
     *out = c;
@@ -394,6 +421,36 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         return launch_gemm(a, epi, split, s);
     };
 
+    const bool want_mega = c->mode == SSSD_MODE_PHASES || c->mode == SSSD_MODE_PERSISTENT;  // AUTO: per-operation kernels for now
+    if (want_mega && M <= mega_max_rows()) {
+        MegaArgs a{};
+        a.D = D; a.io = io; a.layers = W.layer_tab;
+        a.embed = c->embed; a.lm_head = c->lm_head; a.final_norm = c->final_norm;
+        a.X = W.X; a.ssq = W.ssq;
+        for (int i = 0; i < 4; ++i) { a.A[i] = W.mega_A[i]; a.A_stride[i] = W.mega_stride[i]; a.A_half[i] = W.mega_half[i]; }
+        a.Qp = W.Qp; a.Qp_lo = W.Qp_lo; a.Kc = c->Kc; a.Vc = c->Vc;
+        a.part_o = W.part_o; a.part_ml = W.part_ml; a.part_val = W.part_val; a.part_idx = W.part_idx;
+        a.pos_base = W.pos_base; a.err_flag = W.err_flag; a.that_dbg = W.that_dbg; a.rope_cs = W.rope_cs;
+        a.bar = W.bar; a.dbg_logits = c->dbg_logits; a.dbg_hidden = c->dbg_hidden;
+        a.tstamps = c->prof_on ? W.tstamps : nullptr;
+        a.kv_layer_elems = c->S.kv_layer_elems; a.q_rows_pad = c->S.q_rows_pad;
+        const int n_phases = 3 + 6 * D.L;
+        int per_cu = 0;
+        bool persistent = c->mode != SSSD_MODE_PHASES && c->coop_ok;
+        if (persistent && (mega_occupancy(M, &per_cu) != hipSuccess || per_cu < 1)) persistent = false;
+        Prof p(c, s, SSSD_PROF_STEP);
+        if (persistent) {
+            HIP_TRY(hipMemsetAsync(W.bar, 0, 8, s));
+            a.phase_lo = 0; a.phase_hi = n_phases;
+            HIP_TRY(launch_mega(a, c->n_cu, true, s));
+        } else {
+            for (int ph = 0; ph < n_phases; ++ph) {
+                a.phase_lo = ph; a.phase_hi = ph + 1;
+                HIP_TRY(launch_mega(a, c->n_cu, false, s));
+            }
+        }
+        return SSSD_OK;
+    }
     {
         Prof p(c, s, SSSD_PROF_ELEM);
         HIP_TRY(launch_embed(D, io, c->embed, W.X, W.pos_base, W.err_flag, s));
@@ -455,8 +512,15 @@ int sssd_verify_sync(sssd_ctx *c, void *stream)
     if (!valid(c)) return SSSD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     int32_t flag = 0;
+    unsigned bar[2] = {0, 0};
     HIP_TRY(hipMemcpyAsync(&flag, c->W.err_flag, 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(bar, c->W.bar, 8, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if (bar[1]) {
+        HIP_TRY(hipMemsetAsync(c->W.bar, 0, 8, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        return SSSD_ETIMEOUT;
+    }
     if (flag) {
         HIP_TRY(hipMemsetAsync(c->W.err_flag, 0, 4, s));
         HIP_TRY(hipStreamSynchronize(s));
@@ -490,12 +554,28 @@ int sssd_kv_export(sssd_ctx *c, int32_t layer, int32_t b, int32_t t0, int32_t n_
     return kv_copy(c, layer, b, t0, n_rows, k_dst, v_dst, false, stream);
 }
 
+int sssd_verify_set_mode(sssd_ctx *c, int32_t mode)
+{
+    if (!valid(c) || mode < SSSD_MODE_AUTO || mode > SSSD_MODE_PERSISTENT) return SSSD_EINVAL;
+    c->mode = mode;
+    return SSSD_OK;
+}
+
 int sssd_profile_enable(sssd_ctx *c, int32_t on)
 {
     if (!valid(c)) return SSSD_EINVAL;
     c->prof_on = on != 0;
     c->prof_used = 0;
     for (int i = 0; i < SSSD_PROF_CLASSES; ++i) { c->prof_ms[i] = 0; c->prof_n[i] = 0; }
+    return SSSD_OK;
+}
+
+int sssd_profile_phases(sssd_ctx *c, void *stream, uint64_t *ticks, int32_t n)
+{
+    if (!valid(c) || !ticks || n < 2 * (4 + 6 * c->D.L)) return SSSD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(ticks, c->W.tstamps, (size_t)(n < 2 * (4 + 6 * c->D.L) + 256 ? 2 * (4 + 6 * c->D.L) : 2 * (4 + 6 * c->D.L) + 256) * 8, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
     return SSSD_OK;
 }
 

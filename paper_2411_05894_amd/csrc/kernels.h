@@ -75,3 +75,37 @@ struct AttnArgs {
     int B, k;
 };
 hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s);
+
+// ------------------------------------------------- persistent step kernel ----
+struct LayerPtrs {
+    const uint16_t *wq, *wk, *wv, *wo, *wg, *wu, *wd;  // packed
+    const uint16_t *attn_norm, *mlp_norm;
+};
+
+enum { AK_QKV = 0, AK_ATT = 1, AK_GU = 2, AK_F = 3 };  // input of QKV / LM head, attention output, input of gate/up, SwiGLU output
+
+struct MegaArgs {
+    Dims D;
+    StepIO io;
+    const LayerPtrs *layers;  // device array [L]
+    const uint16_t *embed, *lm_head, *final_norm;
+    float *X, *ssq;           // residual stream [M][h]; sums of squares per 16 columns, [2L+1 versions][48][h/16]
+    uint16_t *A[4];           // packed bf16 operand buffers by role (AK_*), [versions][hi half | lo half]
+    size_t A_stride[4];       // bf16 elements per version
+    size_t A_half[4];         // bf16 elements of the hi half (the lo half follows)
+    uint16_t *Qp, *Qp_lo, *Kc, *Vc;
+    float *part_o, *part_ml, *part_val;
+    int *part_idx;
+    int32_t *pos_base, *err_flag, *that_dbg;
+    const float *rope_cs;
+    unsigned *bar;            // [0] barrier arrivals, [1] give-up flag
+    float *dbg_logits, *dbg_hidden;
+    unsigned long long *tstamps;  // optional: constant-rate clock of workgroup 0 at the start of every phase, and at the end
+    size_t kv_layer_elems;
+    int q_rows_pad;
+    int phase_lo, phase_hi;   // phases to run; more than one needs a cooperative launch
+};
+
+int mega_max_rows();
+hipError_t mega_occupancy(int M, int *blocks_per_cu);
+hipError_t launch_mega(const MegaArgs &a, int grid, bool cooperative, hipStream_t s);

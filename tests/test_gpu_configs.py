@@ -106,3 +106,60 @@ def test_cfg4_8b_b4_ctx32768_k8():
     err, ex, rows = compare_step(gpu, ref, tokens, seqs=[2])
     progress(f"cfg4: max logit err {err:.2e}, exempt rows {ex}/{rows}")
     p.ctx.sssd_verify_destroy()
+
+
+@pytest.mark.timeout(900)
+def test_cfg5_70b_b16_ctx2048_k8():
+    """Config 5: Llama-3-70B shape (141 GB of bf16 weights, reordered in place), B=16, context
+    2048, k=8.  The oracle recomputes rows 0..4 of sequence 7 (row j never depends on later
+    rows), streaming the weights layer by layer from the device copy before the library
+    reorders it."""
+    s = MODEL_SHAPES["70b"]
+    B, k, ctx, seed, sample, k_ref = 16, 8, 2048, 6, 7, 4
+    dev = torch.device(DEV)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 170e9:
+        pytest.skip("needs ~165 GB of free device memory")
+    max_seq = ctx + k + 1
+    tokens = uniform_int(seed, TensorId.TOKENS, (B, k + 1), 0, s.vocab - 1)
+    lens = torch.full((B,), ctx, dtype=torch.int32)
+    g = {n: make_weight(seed, n, tid, shp, device=dev) for n, tid, shp in global_weight_specs(s)}
+    om = oracle.OracleModel(s, [None] * s.n_layers, {n: t.cpu() for n, t in g.items()}, 1, max_seq)
+    tok_ref = tokens[sample: sample + 1, : k_ref + 1].contiguous()
+    x = om.embed(tok_ref)
+    layers = []
+    t0 = time.time()
+    for l in range(s.n_layers):
+        lw = {n: make_weight(seed, n, TensorId.layer(l, slot), shp, device=dev) for n, slot, shp in layer_weight_specs(s)}
+        layers.append(lw)
+        K, V = make_kv_prefill(seed * 1000 + sample, l, (s.n_kv_heads, ctx, s.head_dim), device=dev)
+        om.K[l, 0, :, :ctx] = K.cpu()
+        om.V[l, 0, :, :ctx] = V.cpu()
+        om.layers[l] = {n: t.cpu() for n, t in lw.items()}
+        om.layer_verify(l, x, lens[sample: sample + 1], 1, k_ref)
+        om.layers[l] = None
+        if l % 8 == 7:
+            progress(f"cfg5: oracle through layer {l} ({time.time() - t0:.0f}s)")
+    ref_logits = om.lm_head(x).view(1, k_ref + 1, -1)
+    that = torch.tensor([[oracle.argmax(ref_logits[0, j]) for j in range(k_ref + 1)]], dtype=torch.int32)
+    a, n = oracle.accept(tok_ref[0].tolist(), that[0].tolist())
+    ref = {"logits": ref_logits, "that": that, "accepted_len": torch.tensor([a]), "next_token": torch.tensor([n])}
+    del om
+    progress("cfg5: oracle done; initialising the library in place")
+    ctx_ = sv.VerifyContext(sv.make_config(s, B, k, max_seq), layers, g, in_place=True)
+    for b in range(B):
+        for l in range(s.n_layers):
+            K, V = make_kv_prefill(seed * 1000 + b, l, (s.n_kv_heads, ctx, s.head_dim), device=dev)
+            ctx_.sssd_kv_import(l, b, 0, K, V)
+        torch.cuda.synchronize()
+    progress("cfg5: prefilled")
+    logits = torch.zeros(B * (k + 1), s.vocab, dtype=torch.float32, device=dev)
+    ctx_.sssd_debug_outputs(logits, None)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    ctx_.sssd_verify_step(tokens.to(dev), lens.to(dev), acc, nxt)
+    assert ctx_.sssd_verify_sync() == 0
+    gpu = {"logits": logits.cpu().view(B, k + 1, -1), "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
+    err, ex, rows = compare_step(gpu, ref, tokens, seqs=[sample])
+    progress(f"cfg5: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+    ctx_.sssd_verify_destroy()
