@@ -173,59 +173,74 @@ __device__ __forceinline__ void load_positions(CArgs &a, RowInfo &ri)
     __syncthreads();
 }
 
-enum { MEPI_QKV = 0, MEPI_RESID = 1, MEPI_SWIGLU = 2, MEPI_LM = 3 };
-enum { G_QKV = 0, G_O = 1, G_GATEUP = 2, G_DOWN = 3, G_LM = 4 };
+// Phases of the step, in execution order (per layer: QKV .. DOWN).
+enum { PK_EMBED = 0, PK_QKV, PK_ATT, PK_COMB, PK_O, PK_GU, PK_DOWN, PK_LM, PK_ACCEPT, PK_NONE };
+
+__device__ __forceinline__ void decode_phase(int ph, int L, int &kind, int &layer)
+{
+    layer = 0;
+    if (ph == 0) kind = PK_EMBED;
+    else if (ph == 1 + 6 * L) kind = PK_LM;
+    else if (ph == 2 + 6 * L) kind = PK_ACCEPT;
+    else if (ph > 2 + 6 * L) kind = PK_NONE;
+    else { layer = (ph - 1) / 6; kind = PK_QKV + (ph - 1) % 6; }
+}
+__device__ __forceinline__ bool is_gemm(int kind) { return kind == PK_QKV || kind == PK_O || kind == PK_GU || kind == PK_DOWN || kind == PK_LM; }
+// Output tiles per task: 2 for the paired tiles of QKV (rotary partners) and gate/up, and for the
+// LM head (halves its activation re-reads); 1 for O and down, which have only h/16 tiles.
+__device__ __forceinline__ int tiles_per_task(int kind) { return (kind == PK_O || kind == PK_DOWN) ? 1 : 2; }
 
 struct GemmDesc {
     const u32x4 *A_hi, *A_lo;
     int KT;                 // k tiles
     int n_tasks;
-    const u32x4 *W[3];      // QKV: wq, wk, wv; SWIGLU: gate, up; others: W[0]
-    int NT;                 // n tiles of W[0] (RESID / LM)
-    const uint16_t *gamma_next;  // RESID: gains of the norm that consumes the updated stream
+    const u32x4 *W[3];      // QKV: wq, wk, wv; gate/up: gate, up; others: W[0]
+    int NT;                 // n tiles of W[0] (O, down, LM head)
+    const uint16_t *gamma_next;  // O, down: gains of the norm that consumes the updated stream
     const float *ssq_in;         // sums of squares of the stream this GEMM consumes (QKV, gate/up, LM head)
-    float *ssq_out;              // RESID: sums of squares of the updated stream
-    uint16_t *out_hi, *out_lo;   // RESID / SWIGLU: packed operands for the next GEMM
-    int layer;
+    float *ssq_out;              // O, down: sums of squares of the updated stream
+    uint16_t *out_hi, *out_lo;   // O, down, gate/up: packed operands for the next GEMM
+    int layer, kind;
 };
 
 // Operand buffers are versioned: every (layer, role) has its own copy, written in exactly one
 // phase and read only after the barrier that follows it.  No address is ever read before its
 // final write within a launch, so ordinary cached loads cannot see stale lines and the
 // barrier needs no cache invalidation.
-__device__ __forceinline__ uint16_t *abuf(CArgs &a, int kind, int version) { return a.A[kind] + (size_t)version * a.A_stride[kind]; }
+__device__ __forceinline__ uint16_t *abuf(CArgs &a, int role, int version) { return a.A[role] + (size_t)version * a.A_stride[role]; }
 
-template <int NG> __device__ __forceinline__ GemmDesc make_desc(CArgs &a, int which, int layer)
+__device__ __forceinline__ GemmDesc make_desc(CArgs &a, int kind, int layer)
 {
     GemmDesc g{};
     const auto &D = a.D;
     const int KTh = (D.h + 31) >> 5, KTq = (D.qd + 31) >> 5, KTf = (D.f + 31) >> 5;
     const size_t ssq_stride = (size_t)48 * (D.h >> 4);
     g.layer = layer;
-    auto in = [&](int kind, int version) {
-        g.A_hi = (const u32x4 *)abuf(a, kind, version);
-        g.A_lo = (const u32x4 *)(abuf(a, kind, version) + a.A_half[kind]);
+    g.kind = kind;
+    auto in = [&](int role, int version) {
+        g.A_hi = (const u32x4 *)abuf(a, role, version);
+        g.A_lo = (const u32x4 *)(abuf(a, role, version) + a.A_half[role]);
     };
-    auto out = [&](int kind, int version) {
-        g.out_hi = abuf(a, kind, version);
-        g.out_lo = g.out_hi + a.A_half[kind];
+    auto out = [&](int role, int version) {
+        g.out_hi = abuf(a, role, version);
+        g.out_lo = g.out_hi + a.A_half[role];
     };
-    if (which == G_LM) {
+    if (kind == PK_LM) {
         in(AK_QKV, D.L); g.KT = KTh; g.ssq_in = a.ssq + (size_t)(2 * D.L) * ssq_stride;
-        g.NT = D.V >> 4; g.n_tasks = (g.NT + NG - 1) / NG; g.W[0] = (const u32x4 *)a.lm_head;
+        g.NT = D.V >> 4; g.n_tasks = (g.NT + 1) / 2; g.W[0] = (const u32x4 *)a.lm_head;
     } else {
         const LayerPtrs *lw = a.layers + layer;
-        if (which == G_QKV) {
+        if (kind == PK_QKV) {
             in(AK_QKV, layer); g.KT = KTh; g.ssq_in = a.ssq + (size_t)(2 * layer) * ssq_stride;
             g.W[0] = (const u32x4 *)lw->wq; g.W[1] = (const u32x4 *)lw->wk; g.W[2] = (const u32x4 *)lw->wv;
             g.n_tasks = (D.nq + 2 * D.nkv) * (D.d >> 5);
-        } else if (which == G_O) {
+        } else if (kind == PK_O) {
             in(AK_ATT, layer); g.KT = KTq; out(AK_GU, layer); g.ssq_out = a.ssq + (size_t)(2 * layer + 1) * ssq_stride;
             g.W[0] = (const u32x4 *)lw->wo; g.NT = D.h >> 4; g.n_tasks = g.NT; g.gamma_next = lw->mlp_norm;
-        } else if (which == G_GATEUP) {
+        } else if (kind == PK_GU) {
             in(AK_GU, layer); g.KT = KTh; out(AK_F, layer); g.ssq_in = a.ssq + (size_t)(2 * layer + 1) * ssq_stride;
             g.W[0] = (const u32x4 *)lw->wg; g.W[1] = (const u32x4 *)lw->wu; g.n_tasks = D.f >> 4;
-        } else {
+        } else {  // PK_DOWN
             in(AK_F, layer); g.KT = KTf; out(AK_QKV, layer + 1); g.ssq_out = a.ssq + (size_t)(2 * layer + 2) * ssq_stride;
             g.W[0] = (const u32x4 *)lw->wd; g.NT = D.h >> 4; g.n_tasks = g.NT;
             g.gamma_next = layer + 1 < D.L ? a.layers[layer + 1].attn_norm : a.final_norm;
@@ -236,28 +251,28 @@ template <int NG> __device__ __forceinline__ GemmDesc make_desc(CArgs &a, int wh
 
 template <int NG> struct TaskTiles {
     const u32x4 *wt[NG];   // per tile: this lane's record of k-tile 0
-    int tile0;             // first output tile (tiles of RESID / LM tasks are consecutive)
-    int kind, head, pair;  // QKV only: 0 = Q, 1 = K, 2 = V; head within its kind; tile pair within the head
+    int tile0;             // first output tile (tiles of O / down / LM-head tasks are consecutive)
+    int qkind, head, pair; // QKV only: 0 = Q, 1 = K, 2 = V; head within its kind; tile pair within the head
 };
 
-template <int NG, int EPI, typename DimsT>
+template <int NG, typename DimsT>
 __device__ __forceinline__ TaskTiles<NG> resolve_task(const DimsT &D, const GemmDesc &g, int task, int lane)
 {
     TaskTiles<NG> t;
-    t.kind = t.head = t.pair = 0;
+    t.qkind = t.head = t.pair = 0;
     const int KT = g.KT;
-    if (EPI == MEPI_QKV) {
+    if (NG == 2 && g.kind == PK_QKV) {
         const int TH = D.d >> 4, per_head = TH >> 1;
         int head = task / per_head;
         t.pair = task % per_head;
         const u32x4 *Wm = g.W[0];
-        if (head >= D.nq + D.nkv) { t.kind = 2; head -= D.nq + D.nkv; Wm = g.W[2]; }
-        else if (head >= D.nq) { t.kind = 1; head -= D.nq; Wm = g.W[1]; }
+        if (head >= D.nq + D.nkv) { t.qkind = 2; head -= D.nq + D.nkv; Wm = g.W[2]; }
+        else if (head >= D.nq) { t.qkind = 1; head -= D.nq; Wm = g.W[1]; }
         t.head = head;
         t.tile0 = head * TH + t.pair;
         t.wt[0] = Wm + (size_t)t.tile0 * KT * 64 + lane;
         t.wt[NG - 1] = Wm + (size_t)(t.tile0 + per_head) * KT * 64 + lane;   // rotary partner tile
-    } else if (EPI == MEPI_SWIGLU) {
+    } else if (NG == 2 && g.kind == PK_GU) {
         t.tile0 = task;
         t.wt[0] = g.W[0] + (size_t)task * KT * 64 + lane;
         t.wt[NG - 1] = g.W[1] + (size_t)task * KT * 64 + lane;
@@ -272,77 +287,81 @@ __device__ __forceinline__ TaskTiles<NG> resolve_task(const DimsT &D, const Gemm
     return t;
 }
 
-// k-tiles per pipeline step: about 96 registers of loads (W plus hi/lo activations) in flight per wave.
-__host__ __device__ constexpr int step_tiles(int MT, int NG) { return 24 / (NG + 2 * MT) > 2 ? 24 / (NG + 2 * MT) : 2; }
-constexpr int WBUF = 16;  // 16-byte registers that carry weight tiles of one step (NG * KR <= 16), also across a barrier
+// The k-tiles a wave holds in flight: a ring of RING slots, each one k-tile of every tile of
+// the task (weights) plus the hi/lo activation tiles of that k-tile.  A slot is refilled with
+// the k-tile RING positions ahead right after it is consumed, so loads are issued continuously.
+__host__ __device__ constexpr int ring_slots(int MT) { return MT == 1 ? 8 : 4; }
+constexpr int WRING = 16;  // weight registers of the ring (RING * 2 tiles at most); they also carry
+                           // the first k-tiles of the NEXT phase across the barrier
 
-// Weight loads of one step: KR k-tiles from kt of every tile of the task.  k-tiles past the
-// wave's range re-read its last tile (their activations are zeroed at use).
-template <int NG, int KR>
-__device__ __forceinline__ void issue_w(const TaskTiles<NG> &tt, int kt, int kt1, u32x4 (&wbuf)[WBUF])
-{
-#pragma unroll
-    for (int u = 0; u < KR; ++u) {
-        const int ktc = kt + u < kt1 ? kt + u : kt1 - 1;
-#pragma unroll
-        for (int i = 0; i < NG; ++i) wbuf[i * KR + u] = __builtin_nontemporal_load(tt.wt[i] + (size_t)ktc * 64);
-    }
-}
-
-template <int MT, int KR>
-__device__ __forceinline__ void issue_x(const GemmDesc &g, int kt, int kt1, int lane, u32x4 (&xh)[MT][KR], u32x4 (&xl)[MT][KR])
-{
-#pragma unroll
-    for (int u = 0; u < KR; ++u) {
-        const int ktc = kt + u < kt1 ? kt + u : kt1 - 1;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            xh[mt][u] = g.A_hi[((size_t)mt * g.KT + ktc) * 64 + lane];
-            xl[mt][u] = g.A_lo[((size_t)mt * g.KT + ktc) * 64 + lane];
-        }
-    }
-}
-
-// Before a barrier: put the weights of the first step of the NEXT GEMM phase in flight.  They
-// do not depend on anything the step computes, so HBM keeps streaming through the barrier.
-template <int MT, int NG, int EPI>
-__device__ __forceinline__ void prefetch_w(CArgs &a, int which, int layer, u32x4 (&wbuf)[WBUF])
-{
-    constexpr int KR = step_tiles(MT, NG);
-    const GemmDesc g = make_desc<NG>(a, which, layer);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int kt0 = (int)(((long)g.KT * wave) / WAVES), kt1 = (int)(((long)g.KT * (wave + 1)) / WAVES);
-    if ((int)blockIdx.x < g.n_tasks && kt0 < kt1) {
-        const TaskTiles<NG> tt = resolve_task<NG, EPI>(a.D, g, blockIdx.x, lane);
-        issue_w<NG, KR>(tt, kt0, kt1, wbuf);
-    }
-}
-
-struct NoPrefetch {
-    __device__ __forceinline__ void operator()(u32x4 (&)[WBUF]) const {}
+struct KRange {
+    int kt0, kt1;   // this wave's k-tiles
+    int nk_pad;     // k-tiles walked per task (same for every wave), a multiple of RING
 };
+template <int RING> __device__ __forceinline__ KRange wave_range(int KT)
+{
+    const int wave = threadIdx.x >> 6;
+    KRange r;
+    r.kt0 = (int)(((long)KT * wave) / WAVES);
+    r.kt1 = (int)(((long)KT * (wave + 1)) / WAVES);
+    const int widest = (KT + WAVES - 1) / WAVES;
+    r.nk_pad = (widest + RING - 1) / RING * RING;
+    return r;
+}
+
+// Weight loads of ring slot j at k-tile ktb + j for the tiles of tt (k-tiles past the wave's
+// range re-read its last tile; their activations are zeroed at use).
+template <int NG, int RING>
+__device__ __forceinline__ void issue_w_slot(const TaskTiles<NG> &tt, int ktb, int j, const KRange &kr, u32x4 (&wr)[WRING])
+{
+    const int ktc = ktb + j < kr.kt1 ? ktb + j : kr.kt1 - 1;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) wr[j * NG + i] = __builtin_nontemporal_load(tt.wt[i] + (size_t)ktc * 64);
+}
+
+// Before a barrier: put the weights of the first ring of the NEXT GEMM phase in flight.  They
+// do not depend on anything the step computes, so HBM keeps streaming through the barrier.
+template <int MT> __device__ __forceinline__ void prefetch_next_w(CArgs &a, int kind, int layer, u32x4 (&wr)[WRING])
+{
+    constexpr int RING = ring_slots(MT);
+    if (!is_gemm(kind)) return;
+    const GemmDesc g = make_desc(a, kind, layer);
+    const KRange kr = wave_range<RING>(g.KT);
+    const int lane = threadIdx.x & 63;
+    if ((int)blockIdx.x >= g.n_tasks || kr.kt0 >= kr.kt1) return;
+    if (tiles_per_task(kind) == 1) {
+        const TaskTiles<1> tt = resolve_task<1>(a.D, g, blockIdx.x, lane);
+#pragma unroll
+        for (int j = 0; j < RING; ++j) issue_w_slot<1, RING>(tt, kr.kt0, j, kr, wr);
+    } else {
+        const TaskTiles<2> tt = resolve_task<2>(a.D, g, blockIdx.x, lane);
+#pragma unroll
+        for (int j = 0; j < RING; ++j) issue_w_slot<2, RING>(tt, kr.kt0, j, kr, wr);
+    }
+}
 
 // Cross-wave reduction of the K split through LDS, then the phase's epilogue.
-template <int MT, int NG, int EPI>
+template <int MT, int NG>
 __device__ __forceinline__ void gemm_epilogue(CArgs &a, const GemmDesc &g, const TaskTiles<NG> &tt,
                                               f32x4 (&acc)[NG][MT], float *red, const RowInfo &ri)
 {
     const auto &D = a.D;
     const int M = a.io.B * (a.io.k + 1);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    constexpr int NOUT = (EPI == MEPI_QKV || EPI == MEPI_SWIGLU) ? 1 : NG;  // paired tiles share a thread
-    constexpr int ITERS = (NOUT * MT * 256 + THREADS - 1) / THREADS;
+    const bool paired = NG == 2 && g.kind != PK_LM;   // QKV, gate/up: both tiles of a task meet in one thread
+    const int n_out = (paired ? 1 : NG) * MT * 256;
+    constexpr int ITERS = (NG * MT * 256 + THREADS - 1) / THREADS;
 
     // The residual epilogue's inputs do not depend on the reduction: fetch them first.
     float xprev[ITERS], gnext[ITERS];
-    if (EPI == MEPI_RESID) {
+    if (NG == 1) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int o = threadIdx.x + it * THREADS;
-            const int i0 = o / (MT * 256), rem = o % (MT * 256);
+            const int rem = o % (MT * 256);
             const int mt = rem >> 8, r = (rem >> 6) & 3, l = rem & 63;
-            const int m = mt * 16 + 4 * (l >> 4) + r, nt = tt.tile0 + i0, n = nt * 16 + (l & 15);
-            const bool live = o < NOUT * MT * 256 && m < M && nt < g.NT;
+            const int m = mt * 16 + 4 * (l >> 4) + r, nt = tt.tile0, n = nt * 16 + (l & 15);
+            const bool live = o < n_out && m < M && nt < g.NT;
             xprev[it] = live ? a.X[(size_t)m * D.h + n] : 0.f;   // a tile of the stream always belongs to the same workgroup
             gnext[it] = live ? bf16_to_f32(g.gamma_next[n]) : 0.f;
         }
@@ -359,18 +378,34 @@ __device__ __forceinline__ void gemm_epilogue(CArgs &a, const GemmDesc &g, const
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int o = threadIdx.x + it * THREADS;
-        if (o >= NOUT * MT * 256) break;   // whole waves leave together (256 is a multiple of 64)
+        if (o >= n_out) break;   // whole waves leave together (256 is a multiple of 64)
         const int i0 = o / (MT * 256), rem = o % (MT * 256);
         const int mt = rem >> 8, r = (rem >> 6) & 3, l = rem & 63;
         float v0 = 0.f, v1 = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) {
             v0 += red[((w * NG + i0) * MT + mt) * 256 + r * 64 + l];
-            if (NOUT != NG) v1 += red[((w * NG + (NG - 1)) * MT + mt) * 256 + r * 64 + l];
+            if (NG == 2) v1 += red[((w * NG + 1) * MT + mt) * 256 + r * 64 + l];   // used by paired tasks only
         }
         const int m = mt * 16 + 4 * (l >> 4) + r, c = l & 15;
         const bool valid = m < M;
-        if (EPI == MEPI_QKV) {
+        if (NG == 1) {   // O, down: residual update, operands and sums of squares for the next norm
+            const int nt = tt.tile0, n = nt * 16 + c;
+            float xn = 0.f;
+            if (valid && nt < g.NT) {
+                xn = xprev[it] + v0;
+                a.X[(size_t)m * D.h + n] = xn;
+                uint16_t hi, lo;
+                split_bf16(xn * gnext[it], hi, lo);
+                const size_t idx = packed_index(m, n, (D.h + 31) >> 5);
+                g.out_hi[idx] = hi;
+                g.out_lo[idx] = lo;
+            }
+            float ss = xn * xn;
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 16);
+            if (valid && nt < g.NT && c == 0) g.ssq_out[(size_t)m * (D.h >> 4) + nt] = ss;
+        } else if (g.kind == PK_QKV) {
             if (valid) {
                 const float rs = ri.rstd[m];
                 v0 *= rs;
@@ -379,10 +414,10 @@ __device__ __forceinline__ void gemm_epilogue(CArgs &a, const GemmDesc &g, const
                 const int pos = ri.pos[m];
                 const int half = D.d >> 1, ch = tt.pair * 16 + c;  // channel of v0; v1 is ch + half
                 const size_t slab = (size_t)g.layer * a.kv_layer_elems + (size_t)b * D.nkv * D.seq_pad * D.d;
-                if (tt.kind < 2) {
+                if (tt.qkind < 2) {
                     const float2 cs = *reinterpret_cast<const float2 *>(a.rope_cs + ((size_t)pos * half + ch) * 2);
                     const float y0 = v0 * cs.x - v1 * cs.y, y1 = v0 * cs.y + v1 * cs.x;
-                    if (tt.kind == 0) {
+                    if (tt.qkind == 0) {
                         const int kvh = tt.head / D.g, hl = tt.head % D.g, rr = j * D.g + hl;
                         const size_t qs = ((size_t)b * D.nkv + kvh) * a.q_rows_pad * D.d;
                         uint16_t h0, l0, h1, l1;
@@ -402,23 +437,7 @@ __device__ __forceinline__ void gemm_epilogue(CArgs &a, const GemmDesc &g, const
                     vv[vcache_index(pos, ch + half, D.d)] = f32_to_bf16(v1);
                 }
             }
-        } else if (EPI == MEPI_RESID) {
-            const int nt = tt.tile0 + i0, n = nt * 16 + c;
-            float xn = 0.f;
-            if (valid && nt < g.NT) {
-                xn = xprev[it] + v0;
-                a.X[(size_t)m * D.h + n] = xn;
-                uint16_t hi, lo;
-                split_bf16(xn * gnext[it], hi, lo);
-                const size_t idx = packed_index(m, n, (D.h + 31) >> 5);
-                g.out_hi[idx] = hi;
-                g.out_lo[idx] = lo;
-            }
-            float ss = xn * xn;
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 16);
-            if (valid && nt < g.NT && c == 0) g.ssq_out[(size_t)m * (D.h >> 4) + nt] = ss;
-        } else if (EPI == MEPI_SWIGLU) {
+        } else if (g.kind == PK_GU) {
             if (valid) {
                 const float rs = ri.rstd[m];
                 const float gt = v0 * rs, up = v1 * rs;
@@ -429,7 +448,7 @@ __device__ __forceinline__ void gemm_epilogue(CArgs &a, const GemmDesc &g, const
                 g.out_hi[idx] = hi;
                 g.out_lo[idx] = lo;
             }
-        } else {  // MEPI_LM
+        } else {  // PK_LM: two independent tiles per task
             const int nt = tt.tile0 + i0, n = nt * 16 + c;
             const bool live = valid && nt < g.NT;
             const float logit = live ? v0 * ri.rstd[m] : -INFINITY;
@@ -452,74 +471,91 @@ __device__ __forceinline__ void gemm_epilogue(CArgs &a, const GemmDesc &g, const
 }
 
 // One GEMM phase.  A task is NG output tiles (16 columns each) over the full K; the waves of
-// the workgroup split K and reduce through LDS in fixed order.  Each wave walks its
-// (task, k-chunk) steps with the loads of the next step already in flight while it
-// multiplies the current one and while the workgroup reduces a finished task.  With
-// `prefetched`, the weights of the first step were put in flight before the barrier that
-// precedes the phase; `next` puts those of the following phase in flight at the end.
-template <int MT, int NG, int EPI, typename Next>
-__device__ __forceinline__ void phase_gemm(CArgs &a, int which, int layer, float *red, RowInfo &ri, u32x4 (&wbuf)[WBUF],
-                                           bool prefetched, Next next)
+// the workgroup split K and reduce through LDS in fixed order.  `prefetched`: the weights of
+// the first ring were put in flight before the barrier that precedes the phase.  At its end
+// the phase puts the first ring of phase (next_kind, next_layer) in flight.
+template <int MT, int NG>
+__device__ __forceinline__ void phase_gemm(CArgs &a, int kind, int layer, float *red, RowInfo &ri, u32x4 (&wr)[WRING],
+                                           bool prefetched, int next_kind, int next_layer)
 {
-    constexpr int KR = step_tiles(MT, NG);
-    static_assert(NG * KR <= WBUF, "step does not fit the weight registers");
-    const GemmDesc g = make_desc<NG>(a, which, layer);
+    constexpr int RING = ring_slots(MT);
+    static_assert(RING * NG <= WRING, "ring does not fit the weight registers");
+    const GemmDesc g = make_desc(a, kind, layer);
     const auto &D = a.D;
     const int M = a.io.B * (a.io.k + 1);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int kt0 = (int)(((long)g.KT * wave) / WAVES), kt1 = (int)(((long)g.KT * (wave + 1)) / WAVES);
+    const int lane = threadIdx.x & 63;
+    const KRange kr = wave_range<RING>(g.KT);
+    const bool has_k = kr.kt0 < kr.kt1;
     const int n_mine = (int)blockIdx.x < g.n_tasks ? (g.n_tasks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+    const int ipt = kr.nk_pad / RING;          // ring turns per task
+    const int n_turns = n_mine * ipt;
 
-    u32x4 xh[MT][KR], xl[MT][KR];
-    TaskTiles<NG> tt = resolve_task<NG, EPI>(D, g, blockIdx.x, lane);
-    if (n_mine > 0 && kt0 < kt1) {
-        if (!prefetched) issue_w<NG, KR>(tt, kt0, kt1, wbuf);
-        issue_x<MT, KR>(g, kt0, kt1, lane, xh, xl);
+    u32x4 xh[RING][MT], xl[RING][MT];
+    auto issue_x_slot = [&](int ktb, int j) {
+        const int ktc = ktb + j < kr.kt1 ? ktb + j : kr.kt1 - 1;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            xh[j][mt] = g.A_hi[((size_t)mt * g.KT + ktc) * 64 + lane];
+            xl[j][mt] = g.A_lo[((size_t)mt * g.KT + ktc) * 64 + lane];
+        }
+    };
+
+    TaskTiles<NG> tt = resolve_task<NG>(D, g, blockIdx.x, lane);
+    if (n_mine > 0 && has_k) {
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+            if (!prefetched) issue_w_slot<NG, RING>(tt, kr.kt0, j, kr, wr);
+            issue_x_slot(kr.kt0, j);
+        }
     }
-    if (EPI != MEPI_RESID) load_rstd<MT>(a, g.ssq_in, M, ri);
+    if (NG == 2) load_rstd<MT>(a, g.ssq_in, M, ri);
     __syncthreads();
     if (n_mine == 0) {
-        next(wbuf);
+        prefetch_next_w<MT>(a, next_kind, next_layer, wr);
         return;
     }
 
-    for (int ti = 0; ti < n_mine; ++ti) {
-        f32x4 acc[NG][MT];
+    f32x4 acc[NG][MT];
+    TaskTiles<NG> tn = tt;
+    for (int turn = 0; turn < n_turns; ++turn) {
+        const int sub = turn % ipt;
+        if (sub == 0) {
 #pragma unroll
-        for (int i = 0; i < NG; ++i)
+            for (int i = 0; i < NG; ++i)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[i][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        TaskTiles<NG> tn = tt;
-        const bool last_task = ti + 1 == n_mine;
-        if (!last_task) tn = resolve_task<NG, EPI>(D, g, blockIdx.x + (ti + 1) * gridDim.x, lane);
-        for (int kt = kt0; kt < kt1; kt += KR) {
+                for (int mt = 0; mt < MT; ++mt) acc[i][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        const int ktb = kr.kt0 + sub * RING;
+        // where the slots are refilled from: the next turn of this task, or the first of the next task
+        const bool more = turn + 1 < n_turns;
+        const bool task_ends = sub + 1 == ipt;
+        if (task_ends && more) tn = resolve_task<NG>(D, g, blockIdx.x + (turn + 1) / ipt * gridDim.x, lane);
+        const int ktb_next = task_ends ? kr.kt0 : ktb + RING;
+        if (has_k) {
 #pragma unroll
-            for (int u = 0; u < KR; ++u) {
-                const bool live = kt + u < kt1;
+            for (int j = 0; j < RING; ++j) {
+                const bool live = ktb + j < kr.kt1;
+                const u32x4 z = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    const u32x4 z = u32x4{0u, 0u, 0u, 0u};
-                    const u32x4 h = live ? xh[mt][u] : z, l = live ? xl[mt][u] : z;
+                    const u32x4 h = live ? xh[j][mt] : z, l = live ? xl[j][mt] : z;
 #pragma unroll
                     for (int i = 0; i < NG; ++i) {
-                        acc[i][mt] = mfma(h, wbuf[i * KR + u], acc[i][mt]);
-                        acc[i][mt] = mfma(l, wbuf[i * KR + u], acc[i][mt]);
+                        acc[i][mt] = mfma(h, wr[j * NG + i], acc[i][mt]);
+                        acc[i][mt] = mfma(l, wr[j * NG + i], acc[i][mt]);
                     }
                 }
-            }
-            if (kt + KR < kt1) {
-                issue_w<NG, KR>(tt, kt + KR, kt1, wbuf);
-                issue_x<MT, KR>(g, kt + KR, kt1, lane, xh, xl);
-            } else if (!last_task) {
-                issue_w<NG, KR>(tn, kt0, kt1, wbuf);
-                issue_x<MT, KR>(g, kt0, kt1, lane, xh, xl);
-            } else {
-                next(wbuf);
+                if (more) {
+                    issue_w_slot<NG, RING>(task_ends ? tn : tt, ktb_next, j, kr, wr);
+                    issue_x_slot(ktb_next, j);
+                }
             }
         }
-        if (last_task && kt0 >= kt1) next(wbuf);  // a wave without k-tiles still prefetches
-        gemm_epilogue<MT, NG, EPI>(a, g, tt, acc, red, ri);
-        tt = tn;
+        if (task_ends) {
+            if (!more) prefetch_next_w<MT>(a, next_kind, next_layer, wr);
+            gemm_epilogue<MT, NG>(a, g, tt, acc, red, ri);
+            tt = tn;
+        }
     }
 }
 
@@ -749,7 +785,7 @@ __device__ __noinline__ void phase_accept(CArgs &a)
 
 template <int MT> __global__ __launch_bounds__(THREADS) void verify_mega_kernel(MegaArgs args)
 {
-    extern __shared__ float red[];  // WAVES x (up to 4 tiles) x MT x 256 floats
+    extern __shared__ float red[];  // WAVES x 2 tiles x MT x 256 floats
     __shared__ RowInfo ri;
     (void)args;
     CArgs &a = *(CArgs *)__builtin_amdgcn_kernarg_segment_ptr();
@@ -758,76 +794,58 @@ template <int MT> __global__ __launch_bounds__(THREADS) void verify_mega_kernel(
     const int n_phases = 3 + 6 * D.L;
     const int lo = a.phase_lo, hi = a.phase_hi < n_phases ? a.phase_hi : n_phases;
     const bool pers = lo == 0 && hi == n_phases;   // the whole step in this launch: prefetch across barriers
-    constexpr int LMG = MT == 1 ? 4 : 2;            // tiles per LM-head task, bounded by the LDS reduction buffer
-    u32x4 wbuf[WBUF];
+    const bool stamp = a.tstamps && blockIdx.x == 0 && threadIdx.x == 0;
+    u32x4 wr[WRING];
 #pragma unroll
-    for (int i = 0; i < WBUF; ++i) wbuf[i] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < WRING; ++i) wr[i] = u32x4{0u, 0u, 0u, 0u};
+    if (lo > 0) load_positions(a, ri);   // written by phase 0 of an earlier launch
 
-#define PHASE_BEGIN(ph) if ((ph) >= lo && (ph) < hi) { \
-        if (a.tstamps && blockIdx.x == 0 && threadIdx.x == 0) a.tstamps[ph] = wall_clock64();
-#define PHASE_END(ph) if (a.tstamps && blockIdx.x == 0 && threadIdx.x == 0) a.tstamps[n_phases + 1 + (ph)] = wall_clock64(); \
-        if ((ph) + 1 < hi) { if (!grid_barrier(a.bar, epoch, gridDim.x)) return; } }
-
-    PHASE_BEGIN(0)
-        phase_embed(a);
-        if (pers) prefetch_w<MT, 2, MEPI_QKV>(a, G_QKV, 0, wbuf);
-    PHASE_END(0)
-    if (hi > 1) load_positions(a, ri);   // written by phase 0, constant afterwards
-
-    for (int l = 0; l < D.L; ++l) {
-        const int p0 = 1 + 6 * l;
-        PHASE_BEGIN(p0)
-            phase_gemm<MT, 2, MEPI_QKV>(a, G_QKV, l, red, ri, wbuf, pers, NoPrefetch());
-        PHASE_END(p0)
-        PHASE_BEGIN(p0 + 1)
-            if (D.d == 128) phase_attention<128>(a, ri, l);
-            else phase_attention<64>(a, ri, l);
-        PHASE_END(p0 + 1)
-        PHASE_BEGIN(p0 + 2)
-            phase_combine(a, ri, l);
-#ifdef SSSD_EXPERIMENT_TWICE
-            if (a.tstamps && blockIdx.x == 0 && threadIdx.x == 0) a.tstamps[2 * (n_phases + 1) + l] = wall_clock64();
-            phase_combine(a, ri, l);
-            if (a.tstamps && blockIdx.x == 0 && threadIdx.x == 0) a.tstamps[2 * (n_phases + 1) + 64 + l] = wall_clock64();
-#endif
-            if (pers) prefetch_w<MT, 1, MEPI_RESID>(a, G_O, l, wbuf);
-        PHASE_END(p0 + 2)
-        PHASE_BEGIN(p0 + 3)
-            phase_gemm<MT, 1, MEPI_RESID>(a, G_O, l, red, ri, wbuf, pers,
-                                          [&](u32x4 (&w)[WBUF]) { if (pers) prefetch_w<MT, 2, MEPI_SWIGLU>(a, G_GATEUP, l, w); });
-        PHASE_END(p0 + 3)
-        PHASE_BEGIN(p0 + 4)
-            phase_gemm<MT, 2, MEPI_SWIGLU>(a, G_GATEUP, l, red, ri, wbuf, pers,
-                                           [&](u32x4 (&w)[WBUF]) { if (pers) prefetch_w<MT, 1, MEPI_RESID>(a, G_DOWN, l, w); });
-        PHASE_END(p0 + 4)
-        PHASE_BEGIN(p0 + 5)
-            phase_gemm<MT, 1, MEPI_RESID>(a, G_DOWN, l, red, ri, wbuf, pers, [&](u32x4 (&w)[WBUF]) {
-                if (pers) {
-                    if (l + 1 < D.L) prefetch_w<MT, 2, MEPI_QKV>(a, G_QKV, l + 1, w);
-                    else prefetch_w<MT, LMG, MEPI_LM>(a, G_LM, 0, w);
-                }
-            });
-        PHASE_END(p0 + 5)
-    }
-    PHASE_BEGIN(n_phases - 2)
-        if (a.dbg_hidden) {
-            const int M = a.io.B * (a.io.k + 1);
-            for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < (size_t)M * D.h; i += (size_t)gridDim.x * THREADS)
-                a.dbg_hidden[i] = ld_shared(a.X + i);
+    for (int ph = lo; ph < hi; ++ph) {
+        int kind, layer, next_kind, next_layer;
+        decode_phase(ph, D.L, kind, layer);
+        decode_phase(ph + 1, D.L, next_kind, next_layer);
+        if (!pers) next_kind = PK_NONE;
+        if (stamp) a.tstamps[ph] = wall_clock64();
+        switch (kind) {
+        case PK_EMBED:
+            phase_embed(a);
+            prefetch_next_w<MT>(a, next_kind, next_layer, wr);
+            break;
+        case PK_QKV: case PK_GU: case PK_LM:
+            if (kind == PK_LM && a.dbg_hidden) {
+                const int M = a.io.B * (a.io.k + 1);
+                for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < (size_t)M * D.h; i += (size_t)gridDim.x * THREADS)
+                    a.dbg_hidden[i] = ld_shared(a.X + i);
+            }
+            phase_gemm<MT, 2>(a, kind, layer, red, ri, wr, pers, next_kind, next_layer);
+            break;
+        case PK_O: case PK_DOWN:
+            phase_gemm<MT, 1>(a, kind, layer, red, ri, wr, pers, next_kind, next_layer);
+            break;
+        case PK_ATT:
+            if (D.d == 128) phase_attention<128>(a, ri, layer);
+            else phase_attention<64>(a, ri, layer);
+            break;
+        case PK_COMB:
+            phase_combine(a, ri, layer);
+            prefetch_next_w<MT>(a, next_kind, next_layer, wr);
+            break;
+        default:
+            phase_accept(a);
+            break;
         }
-        phase_gemm<MT, LMG, MEPI_LM>(a, G_LM, 0, red, ri, wbuf, pers, NoPrefetch());
-    PHASE_END(n_phases - 2)
-    PHASE_BEGIN(n_phases - 1)
-        phase_accept(a);
+        if (stamp) a.tstamps[n_phases + 1 + ph] = wall_clock64();
+        if (ph + 1 < hi) {
+            if (!grid_barrier(a.bar, epoch, gridDim.x)) return;
+            if (ph == 0) load_positions(a, ri);   // written by phase 0, constant afterwards
+        }
     }
-    if (a.tstamps && blockIdx.x == 0 && threadIdx.x == 0) a.tstamps[n_phases] = wall_clock64();
-#undef PHASE_BEGIN
-#undef PHASE_END
+    if (stamp) a.tstamps[n_phases] = wall_clock64();
 }
 
 template <int MT> hipError_t launch_mt(const MegaArgs &a, int grid, bool cooperative, hipStream_t s)
 {
-    const size_t lds = (size_t)WAVES * (MT == 1 ? 4 : 2) * MT * 256 * sizeof(float);
+    const size_t lds = (size_t)WAVES * 2 * MT * 256 * sizeof(float);
     auto kern = verify_mega_kernel<MT>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -847,7 +865,7 @@ int mega_max_rows() { return 48; }
 hipError_t mega_occupancy(int M, int *blocks_per_cu)
 {
     const int mt = (M + 15) / 16;
-    const size_t lds = (size_t)WAVES * (mt == 1 ? 4 : 2) * mt * 256 * sizeof(float);
+    const size_t lds = (size_t)WAVES * 2 * mt * 256 * sizeof(float);
     const void *k = mt == 1 ? (const void *)verify_mega_kernel<1> : mt == 2 ? (const void *)verify_mega_kernel<2> : (const void *)verify_mega_kernel<3>;
     hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
