@@ -139,7 +139,7 @@ def main() -> int:
         ms_per_launch = prof["step"]["ms"] / prof["step"]["launches"]
         bytes_per_launch = bytes_alg["total"] / launches
     else:
-        kname, launches = "gemm_skinny_kernel", prof["gemm"]["launches"] / prof_steps
+        kname, launches = "fused_gemm_kernel", prof["gemm"]["launches"] / prof_steps
         ms_per_launch = prof["gemm"]["ms"] / prof["gemm"]["launches"]
         bytes_per_launch = bytes_alg["weights"] / launches
     achieved = bytes_per_launch / (ms_per_launch * 1e-3) / 1e9

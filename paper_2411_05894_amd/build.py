@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsssd_verify.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "mega.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "mega.hip", "fused.hip"]
 import shlex
 FLAGS = shlex.split(os.environ.get("SSSD_EXTRA_HIPCC_FLAGS", "")) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          # packed-fp32 VALU forms are kept off on the test machines

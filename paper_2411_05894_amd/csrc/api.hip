@@ -20,7 +20,7 @@ struct Buffers {
     float *part_o, *part_ml, *part_val;
     int *part_idx;
     int32_t *pos_base, *err_flag, *that_dbg;
-    float *rope_cs, *ssq;
+    float *rope_cs, *ssq, *ssq1;
     unsigned *bar;
     LayerPtrs *layer_tab;
     unsigned long long *tstamps;
@@ -135,6 +135,7 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.pos_base = (int32_t *)take((size_t)D.max_batch * 4);
     b.err_flag = (int32_t *)take(4);
     b.bar = (unsigned *)take(8);
+    b.ssq1 = (float *)take((size_t)S.m_alloc * (D.h / 16) * 4);
     b.ssq = (float *)take((size_t)(2 * D.L + 1) * 48 * (D.h / 16) * 4);
     {
         // versioned operand buffers of the persistent kernel: 3 row tiles, one copy per (layer, role)
@@ -421,7 +422,65 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         return launch_gemm(a, epi, split, s);
     };
 
-    const bool want_mega = c->mode == SSSD_MODE_PHASES || c->mode == SSSD_MODE_PERSISTENT;  // AUTO: per-operation kernels for now
+    if (c->mode == SSSD_MODE_AUTO) {
+        // Six fused launches per layer (QKV, attention, merge, O, gate/up, down).
+        {
+            Prof p(c, s, SSSD_PROF_ELEM);
+            HIP_TRY(launch_fused_embed(D, io, c->embed, c->layers[0].attn_norm, W.X, W.Ah_hi, W.Ah_lo, W.ssq1, W.pos_base,
+                                       W.err_flag, s));
+        }
+        FusedGemmArgs f{};
+        f.M = M; f.h = D.h; f.d = D.d; f.nq = D.nq; f.nkv = D.nkv; f.seq_pad = D.seq_pad; f.k = k;
+        f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps;
+        f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
+        f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
+        const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
+        auto fgemm = [&](int epi) -> hipError_t {
+            Prof p(c, s, SSSD_PROF_GEMM);
+            return launch_fused_gemm(f, epi, s);
+        };
+        for (int l = 0; l < D.L; ++l) {
+            const LayerW &lw = c->layers[l];
+            uint16_t *Kl = c->Kc + (size_t)l * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)l * c->S.kv_layer_elems;
+            // QKV
+            f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
+            f.W0 = (const u32x4 *)lw.wq; f.W1 = (const u32x4 *)lw.wk; f.W2 = (const u32x4 *)lw.wv;
+            f.n_tasks = (D.nq + 2 * D.nkv) * (D.d / 32); f.NT = 0; f.Kc = Kl; f.Vc = Vl;
+            HIP_TRY(fgemm(FEPI_QKV));
+            {
+                AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
+                Prof p(c, s, SSSD_PROF_ATTN);
+                HIP_TRY(launch_attention(D, a, s));
+            }
+            // O
+            f.A_hi = (const u32x4 *)W.Aq_hi; f.A_lo = (const u32x4 *)W.Aq_lo; f.KT = KTq;
+            f.W0 = (const u32x4 *)lw.wo; f.NT = D.h / 16; f.n_tasks = f.NT; f.gamma_next = lw.mlp_norm;
+            f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
+            HIP_TRY(fgemm(FEPI_RESID));
+            // gate/up
+            f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
+            f.W0 = (const u32x4 *)lw.wg; f.W1 = (const u32x4 *)lw.wu; f.n_tasks = D.f / 16;
+            f.out_hi = W.Af_hi; f.out_lo = W.Af_lo; f.KT_out = KTf;
+            HIP_TRY(fgemm(FEPI_SWIGLU));
+            // down
+            f.A_hi = (const u32x4 *)W.Af_hi; f.A_lo = (const u32x4 *)W.Af_lo; f.KT = KTf;
+            f.W0 = (const u32x4 *)lw.wd; f.NT = D.h / 16; f.n_tasks = f.NT;
+            f.gamma_next = l + 1 < D.L ? c->layers[l + 1].attn_norm : c->final_norm;
+            f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
+            HIP_TRY(fgemm(FEPI_RESID));
+        }
+        if (c->dbg_hidden)
+            HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
+        f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
+        f.W0 = (const u32x4 *)c->lm_head; f.NT = D.V / 16; f.n_tasks = (f.NT + 1) / 2;
+        HIP_TRY(fgemm(FEPI_LM));
+        {
+            Prof p(c, s, SSSD_PROF_ACCEPT);
+            HIP_TRY(launch_accept(D, io, W.part_val, W.part_idx, D.V / 16, W.that_dbg, s));
+        }
+        return SSSD_OK;
+    }
+    const bool want_mega = c->mode == SSSD_MODE_PHASES || c->mode == SSSD_MODE_PERSISTENT;
     if (want_mega && M <= mega_max_rows()) {
         MegaArgs a{};
         a.D = D; a.io = io; a.layers = W.layer_tab;

@@ -159,31 +159,62 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, in
     }
 }
 
-// grid = (g*(k+1) query rows, nkv, B), block = d threads (one per channel).
-__global__ void attn_combine_kernel(Dims D, AttnArgs a, int q_rows_pad)
+// One wave per (sequence, kv head, query row); 4 waves per block.  Lanes first work across
+// chunks (weights), then across channels (values, eight chunks' loads in flight at a time).
+__global__ __launch_bounds__(256) void attn_combine_kernel(Dims D, AttnArgs a, int q_rows_pad)
 {
-    const int r = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, ch = threadIdx.x;
-    const int total = a.pos_base[b] + a.k + 1;
+    const int lane = threadIdx.x & 63, k = a.k;
+    const int R = D.g * (k + 1);
+    const int n_tasks = a.B * D.nkv * R;
+    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (task >= n_tasks) return;
+    const int KTq = (D.qd + 31) >> 5;
+    const int ch = lane * 2;  // head_dim 128: two channels per lane; head_dim 64: lanes 0..31
+    const int r = task % R, kvh = (task / R) % D.nkv, b = task / (R * D.nkv);
+    const int total = a.pos_base[b] + k + 1;
     const int n_splits = (total + D.chunk - 1) / D.chunk;
     const size_t slot0 = ((size_t)b * D.nkv + kvh) * D.max_splits;
     float m_star = NEG_BIG;
-    for (int s = 0; s < n_splits; ++s) m_star = fmaxf(m_star, a.part_ml[((slot0 + s) * q_rows_pad + r) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const size_t row = (slot0 + s) * q_rows_pad + r;
-        const float w = exp2f(a.part_ml[row * 2] - m_star);
-        den += w * a.part_ml[row * 2 + 1];
-        num += w * a.part_o[row * D.d + ch];
+    for (int s = lane; s < n_splits; s += 64) m_star = fmaxf(m_star, a.part_ml[((slot0 + s) * q_rows_pad + r) * 2]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m_star = fmaxf(m_star, __shfl_xor(m_star, off));
+    float den = 0.f, num0 = 0.f, num1 = 0.f;
+    for (int base = 0; base < n_splits; base += 64) {
+        const int s_mine = base + lane;
+        float w_lane = 0.f;
+        if (s_mine < n_splits) {
+            const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((slot0 + s_mine) * q_rows_pad + r) * 2);
+            w_lane = exp2f(ml.x - m_star);
+            den += w_lane * ml.y;
+        }
+        const int n_here = n_splits - base < 64 ? n_splits - base : 64;
+        for (int s0 = 0; s0 < n_here; s0 += 8) {
+            float2 pv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const size_t row = (slot0 + base + s0 + u) * q_rows_pad + r;
+                pv[u] = (s0 + u < n_here && ch < D.d) ? *reinterpret_cast<const float2 *>(a.part_o + row * D.d + ch) : float2{0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float w = __shfl(w_lane, s0 + u);   // lanes past n_here hold 0
+                num0 += w * pv[u].x;
+                num1 += w * pv[u].y;
+            }
+        }
     }
-    const float out = num / den;
-    const int j = r / D.g, hl = r % D.g;
-    const int m = b * (a.k + 1) + j;
-    const int col = (kvh * D.g + hl) * D.d + ch;
-    uint16_t hi, lo;
-    split_bf16(out, hi, lo);
-    const size_t idx = packed_index(m, col, (D.qd + 31) / 32);
-    a.out_hi[idx] = hi;
-    a.out_lo[idx] = lo;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off);
+    if (ch < D.d) {
+        const int j = r / D.g, hl = r % D.g, m = b * (k + 1) + j;
+        const int col = (kvh * D.g + hl) * D.d + ch;
+        uint16_t h0, l0, h1, l1;
+        split_bf16(num0 / den, h0, l0);
+        split_bf16(num1 / den, h1, l1);
+        const size_t idx = packed_index(m, col, KTq);  // col is even: both channels share a lane record
+        a.out_hi[idx] = h0; a.out_hi[idx + 1] = h1;
+        a.out_lo[idx] = l0; a.out_lo[idx + 1] = l1;
+    }
 }
 
 template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, int q_rows_pad, hipStream_t s)
@@ -212,6 +243,7 @@ hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s)
     const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
     hipError_t e = D.d == 128 ? launch_partial<128>(D, a, q_rows_pad, s) : launch_partial<64>(D, a, q_rows_pad, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(D.g * (a.k + 1), D.nkv, a.B), dim3(D.d), 0, s, D, a, q_rows_pad);
+    const int n_tasks = a.B * D.nkv * D.g * (a.k + 1);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3((n_tasks + 3) / 4), dim3(256), 0, s, D, a, q_rows_pad);
     return hipGetLastError();
 }

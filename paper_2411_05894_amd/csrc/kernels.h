@@ -38,6 +38,36 @@ struct StepIO {
     int B, k;
 };
 
+// ------------------------------------------------------------ fused GEMMs ----
+enum FusedEpilogue {
+    FEPI_QKV = 0,    // RMSNorm scale, rotary embedding, Q operand packing, KV append; tasks = rotary tile pairs
+    FEPI_RESID = 1,  // X += acc; packed X*gamma_next; sums of squares per 16 columns; tasks = single tiles
+    FEPI_SWIGLU = 2, // RMSNorm scale, silu(gate)*up, operand packing; tasks = (gate tile, up tile)
+    FEPI_LM = 3      // RMSNorm scale, per-tile arg-max, optional logits; tasks = two consecutive tiles
+};
+
+struct FusedGemmArgs {
+    const u32x4 *A_hi, *A_lo;     // packed activations x*gamma (or attention output / SwiGLU output)
+    const u32x4 *W0, *W1, *W2;    // QKV: wq, wk, wv; SWIGLU: gate, up; else W0
+    int KT, NT, n_tasks, M;       // k tiles, n tiles of W0, workgroups, valid rows
+    int h, d, nq, nkv, seq_pad, k, q_rows_pad, vocab;
+    float eps;
+    const float *ssq_in;          // [M][h/16] sums of squares of the consumed stream (not RESID)
+    float *X, *ssq_out;           // RESID: residual stream [M][h], sums of squares of the updated stream
+    const uint16_t *gamma_next;   // RESID: gains of the norm that consumes the updated stream
+    uint16_t *out_hi, *out_lo;    // RESID (K = h) / SWIGLU (KT_out k-tiles): packed operands of the next GEMM
+    int KT_out;
+    const float *rope_cs;         // QKV
+    const int32_t *pos_base;
+    uint16_t *Qp, *Qp_lo, *Kc, *Vc;  // Kc, Vc: this layer's cache
+    float *logits, *part_val;     // LM
+    int *part_idx;
+};
+hipError_t launch_fused_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
+hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
+                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,
+                              hipStream_t s);
+
 // Validates lens/tokens (sticky flag, safe substitutes) and gathers embedding rows.
 hipError_t launch_embed(const Dims &D, const StepIO &io, const uint16_t *embed, float *X, int32_t *pos_base,
                         int32_t *err_flag, hipStream_t s);

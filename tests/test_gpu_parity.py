@@ -108,7 +108,7 @@ def test_attention_vs_oracle(shape_name, B, k, ctxs):
 
 
 # ----------------------------------------------------- cfg 1: tiny chain ----
-MODES = [pytest.param(sv.SSSD_MODE_KERNELS, id="kernels"), pytest.param(sv.SSSD_MODE_PHASES, id="phases"),
+MODES = [pytest.param(sv.SSSD_MODE_AUTO, id="fused"), pytest.param(sv.SSSD_MODE_KERNELS, id="kernels"), pytest.param(sv.SSSD_MODE_PHASES, id="phases"),
          pytest.param(sv.SSSD_MODE_PERSISTENT, id="persistent")]
 
 
