@@ -20,6 +20,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each
+# calibrated against a 1 GiB copy kernel); source: profiles/verify_step_8b_b1_ctx2048_k8_hbm_traffic.md.
+# Only the workload those runs covered has a figure.
+MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "fused_gemm_kernel"): 120.47e6}
+
 WORKLOADS = {
     # name: (shape, B, ctx spec, k, k sweep)
     "cfg2": dict(shape="8b", B=1, ctx=2048, k=8, sweep=list(range(17)), seed=3),
@@ -40,6 +45,8 @@ def main() -> int:
     ap.add_argument("--sweep-steps", type=int, default=20)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (known traffic) to calibrate rocprofv3 byte counters")
     ap.add_argument("--mode", default="auto", choices=["auto", "kernels", "phases", "persistent"])
     args = ap.parse_args()
     if args.gpus != 1:
@@ -118,6 +125,14 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / n_steps
 
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- the timed region ----
     ms = time_steps(k, args.warmup, args.steps)
     assert ctx.sssd_verify_sync() == 0
@@ -144,7 +159,8 @@ def main() -> int:
         bytes_per_launch = bytes_alg["weights"] / launches
     achieved = bytes_per_launch / (ms_per_launch * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
-                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": None,
+                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((args.workload, k, kname)),
                 "bytes_per_launch": round(bytes_per_launch), "launches_per_step": launches,
                 "avg_launch_us": round(ms_per_launch * 1e3, 2)}
     classes_ms = {n: round(v["ms"] / prof_steps, 4) for n, v in prof.items()}

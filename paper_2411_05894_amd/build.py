@@ -8,6 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsssd_verify.so")
+DRIVER = os.path.join(HERE, "step_driver")
 SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "mega.hip", "fused.hip"]
 import shlex
 FLAGS = shlex.split(os.environ.get("SSSD_EXTRA_HIPCC_FLAGS", "")) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
@@ -26,6 +27,9 @@ def build(jobs: int = 4) -> str:
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    # native driver of the C ABI for profiler runs (plain executable, no Python in the process)
+    subprocess.run(["hipcc", *FLAGS, os.path.join(HERE, "tools", "step_driver.hip"), "-o", DRIVER, "-L" + HERE,
+                    "-lsssd_verify", "-Wl,-rpath,$ORIGIN"], check=True)
     return LIB
 
 

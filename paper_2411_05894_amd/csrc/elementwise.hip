@@ -102,46 +102,45 @@ __global__ void rope_append_kernel(Dims D, const float *qkv, const int32_t *pos_
     }
 }
 
-// grid = B, block = 256.  Row arg-max from the LM head's per-tile partials (lowest id
-// wins ties), then the longest draft prefix the arg-max chain reproduces.
-__global__ __launch_bounds__(256) void accept_kernel(StepIO io, const float *part_val, const int *part_idx, int NT,
-                                                     int32_t *that_dbg)
+// grid = M rows, block = 256.  Row arg-max from the LM head's per-tile partials; the lowest
+// token id wins a tie.
+__global__ __launch_bounds__(256) void row_argmax_kernel(const float *part_val, const int *part_idx, int NT, int32_t *that)
 {
     __shared__ float sv[4];
     __shared__ int si[4];
-    __shared__ int that[32];
-    const int b = blockIdx.x, sq = io.k + 1;
-    for (int j = 0; j < sq; ++j) {
-        const size_t row = (size_t)(b * sq + j) * NT;
-        float bv = -INFINITY;
-        int bi = 0x7FFFFFFF;
-        for (int t = threadIdx.x; t < NT; t += blockDim.x) {
-            const float v = part_val[row + t];
-            const int id = part_idx[row + t];
-            if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
-        }
+    const size_t row = (size_t)blockIdx.x * NT;
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int t = threadIdx.x; t < NT; t += blockDim.x) {
+        const float v = part_val[row + t];
+        const int id = part_idx[row + t];
+        if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
+    }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off);
-            const int oi = __shfl_xor(bi, off);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            for (int w = 1; w < 4; ++w)
-                if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
-            that[j] = bi;
-            if (that_dbg) that_dbg[b * sq + j] = bi;
-        }
-        __syncthreads();
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
     }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        int n = 0;
-        while (n < io.k && io.tokens[b * sq + n + 1] == that[n]) ++n;
-        io.accepted_len[b] = n;
-        io.next_token[b] = that[n];
+        for (int w = 1; w < 4; ++w)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        that[blockIdx.x] = bi;
     }
+}
+
+// One thread per sequence: the longest draft prefix the arg-max chain reproduces, and the bonus token.
+__global__ void accept_kernel(StepIO io, const int32_t *that)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= io.B) return;
+    const int sq = io.k + 1;
+    int n = 0;
+    while (n < io.k && io.tokens[b * sq + n + 1] == that[b * sq + n]) ++n;
+    io.accepted_len[b] = n;
+    io.next_token[b] = that[b * sq + n];
 }
 
 __global__ void rollback_kernel(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens)
@@ -245,10 +244,13 @@ hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *po
 }
 
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
-                         int32_t *that_dbg, hipStream_t s)
+                         int32_t *that, hipStream_t s)
 {
     (void)D;
-    hipLaunchKernelGGL(accept_kernel, dim3(io.B), dim3(256), 0, s, io, part_val, part_idx, NT, that_dbg);
+    hipLaunchKernelGGL(row_argmax_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, part_val, part_idx, NT, that);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(accept_kernel, dim3((io.B + 63) / 64), dim3(64), 0, s, io, that);
     return hipGetLastError();
 }
 
