@@ -28,6 +28,8 @@ struct Buffers {
     size_t mega_stride[4], mega_half[4];
     uint8_t *staging;
     size_t staging_bytes;
+    float *partials;
+    size_t partial_bytes;
 };
 
 struct Sizes {
@@ -153,6 +155,8 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.rope_cs = (float *)take((size_t)D.max_seq * (D.d / 2) * 2 * 4);
     b.staging_bytes = (size_t)64 << 20;
     b.staging = take(b.staging_bytes);
+    b.partial_bytes = stream_gemm_partial_bytes(D, M);
+    b.partials = (float *)take(b.partial_bytes);
     if (B) *B = b;
     return off;
 }
@@ -435,9 +439,11 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
         f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
         const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
+        f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
+        const bool streamer = M <= stream_gemm_max_rows();
         auto fgemm = [&](int epi) -> hipError_t {
             Prof p(c, s, SSSD_PROF_GEMM);
-            return launch_fused_gemm(f, epi, s);
+            return streamer ? launch_stream_gemm(f, epi, s) : launch_fused_gemm(f, epi, s);
         };
         for (int l = 0; l < D.L; ++l) {
             const LayerW &lw = c->layers[l];
@@ -445,7 +451,8 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
             // QKV
             f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
             f.W0 = (const u32x4 *)lw.wq; f.W1 = (const u32x4 *)lw.wk; f.W2 = (const u32x4 *)lw.wv;
-            f.n_tasks = (D.nq + 2 * D.nkv) * (D.d / 32); f.NT = 0; f.Kc = Kl; f.Vc = Vl;
+            f.n_tasks = (D.nq + 2 * D.nkv) * (D.d / 32); f.NT = D.qd / 16; f.Kc = Kl; f.Vc = Vl;
+            f.n_units = f.n_tasks; f.Ntot = D.qd + 2 * D.kd;
             HIP_TRY(fgemm(FEPI_QKV));
             {
                 AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
@@ -455,16 +462,19 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
             // O
             f.A_hi = (const u32x4 *)W.Aq_hi; f.A_lo = (const u32x4 *)W.Aq_lo; f.KT = KTq;
             f.W0 = (const u32x4 *)lw.wo; f.NT = D.h / 16; f.n_tasks = f.NT; f.gamma_next = lw.mlp_norm;
+            f.n_units = f.NT; f.Ntot = D.h;
             f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
             HIP_TRY(fgemm(FEPI_RESID));
             // gate/up
             f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
             f.W0 = (const u32x4 *)lw.wg; f.W1 = (const u32x4 *)lw.wu; f.n_tasks = D.f / 16;
+            f.NT = D.f / 16; f.n_units = f.NT; f.Ntot = 2 * D.f;
             f.out_hi = W.Af_hi; f.out_lo = W.Af_lo; f.KT_out = KTf;
             HIP_TRY(fgemm(FEPI_SWIGLU));
             // down
             f.A_hi = (const u32x4 *)W.Af_hi; f.A_lo = (const u32x4 *)W.Af_lo; f.KT = KTf;
             f.W0 = (const u32x4 *)lw.wd; f.NT = D.h / 16; f.n_tasks = f.NT;
+            f.n_units = f.NT; f.Ntot = D.h;
             f.gamma_next = l + 1 < D.L ? c->layers[l + 1].attn_norm : c->final_norm;
             f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
             HIP_TRY(fgemm(FEPI_RESID));
@@ -473,6 +483,7 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
             HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
         f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
         f.W0 = (const u32x4 *)c->lm_head; f.NT = D.V / 16; f.n_tasks = (f.NT + 1) / 2;
+        f.n_units = f.NT; f.Ntot = D.V;
         HIP_TRY(fgemm(FEPI_LM));
         {
             Prof p(c, s, SSSD_PROF_ACCEPT);

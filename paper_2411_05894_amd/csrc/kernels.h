@@ -62,8 +62,19 @@ struct FusedGemmArgs {
     uint16_t *Qp, *Qp_lo, *Kc, *Vc;  // Kc, Vc: this layer's cache
     float *logits, *part_val;     // LM
     int *part_idx;
+    // weight streamer (stream_gemm.hip)
+    int n_units;                  // epilogue units: rotary tile pairs (QKV), gate/up tile pairs (SWIGLU), tiles (RESID, LM)
+    int Ntot;                     // columns of the concatenated output: (nq+2nkv)*d, 2*ffn, h, vocab
+    int n_cu;                     // compute units of the device
+    float *partials;              // split-K scratch [J][part_rows][Ntot] fp32
+    size_t partial_bytes;
+    int upw, J, part_rows;        // filled in by the launcher: units per workgroup, K slices, rows per slice
 };
 hipError_t launch_fused_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
+// M <= stream_gemm_max_rows(): persistent weight streamer; NT must be the tile count of W0.
+int stream_gemm_max_rows();
+size_t stream_gemm_partial_bytes(const Dims &D, int M);
+hipError_t launch_stream_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
                               uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,
                               hipStream_t s);
