@@ -26,9 +26,11 @@ int sssd_op_pack_weight(const void *w, void *packed, int32_t N, int32_t K, void 
 int sssd_op_pack_activation(const float *x, int32_t M, int32_t K, void *a_hi, void *a_lo, void *stream);
 
 /* Table 2 linear rows: out[M][N] (device fp32, row-major) = X[M][K] . W[N][K]^T with fp32
- * accumulation.  a_lo == NULL uses the bf16 hi part alone. */
+ * accumulation, X = a_hi + a_lo.  scratch: device, at least sssd_op_gemm_scratch_bytes(M, N, K)
+ * bytes (split-K partial sums; may be NULL when that is 0); SSSD_ECAPACITY if it is smaller. */
+size_t sssd_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K,
-                 float *out, void *stream);
+                 float *out, void *scratch, size_t scratch_bytes, void *stream);
 
 /* Table 2 attention row on a context's cache: q device fp32 [B][k+1][n_q_heads][head_dim]
  * (already rotated), lens device int32 [B] (the k+1 new K/V rows of `layer` must already be

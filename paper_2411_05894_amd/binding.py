@@ -75,7 +75,9 @@ def lib() -> C.CDLL:
         l.sssd_op_packed_act_bytes.argtypes = [i32, i32]
         l.sssd_op_pack_weight.argtypes = [vp, vp, i32, i32, vp]
         l.sssd_op_pack_activation.argtypes = [vp, i32, i32, vp, vp, vp]
-        l.sssd_op_gemm.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+        l.sssd_op_gemm_scratch_bytes.argtypes = [i32, i32, i32]
+        l.sssd_op_gemm_scratch_bytes.restype = C.c_size_t
+        l.sssd_op_gemm.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, C.c_size_t, vp]
         l.sssd_op_attention.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
         _lib = l
     return _lib
@@ -226,9 +228,12 @@ def sssd_op_pack_activation(x: torch.Tensor):
     return hi, lo
 
 
-def sssd_op_gemm(a_hi: torch.Tensor, a_lo: Optional[torch.Tensor], w_packed: torch.Tensor, M: int, N: int,
+def sssd_op_gemm(a_hi: torch.Tensor, a_lo: torch.Tensor, w_packed: torch.Tensor, M: int, N: int,
                  K: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     if out is None:
         out = torch.empty(M, N, dtype=torch.float32, device=a_hi.device)
-    _check(lib().sssd_op_gemm(_ptr(a_hi), _ptr(a_lo), _ptr(w_packed), M, N, K, _ptr(out), _stream()), "sssd_op_gemm")
+    nbytes = lib().sssd_op_gemm_scratch_bytes(M, N, K)
+    scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=a_hi.device)
+    _check(lib().sssd_op_gemm(_ptr(a_hi), _ptr(a_lo), _ptr(w_packed), M, N, K, _ptr(out), _ptr(scratch), nbytes,
+                              _stream()), "sssd_op_gemm")
     return out

@@ -440,7 +440,7 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
         const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
         f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
-        const bool streamer = M <= stream_gemm_max_rows();
+        const bool streamer = true;
         auto fgemm = [&](int epi) -> hipError_t {
             Prof p(c, s, SSSD_PROF_GEMM);
             return streamer ? launch_stream_gemm(f, epi, s) : launch_fused_gemm(f, epi, s);
@@ -692,14 +692,23 @@ int sssd_op_pack_activation(const float *x, int32_t M, int32_t K, void *a_hi, vo
     return SSSD_OK;
 }
 
-int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K, float *out,
-                 void *stream)
+size_t sssd_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K)
 {
-    if (!a_hi || !w_packed || !out || M <= 0 || N <= 0 || K <= 0 || N % 16) return SSSD_EINVAL;
-    GemmArgs a{};
+    if (M <= 0 || N <= 0 || K <= 0 || N % 16) return 0;
+    return stream_gemm_scratch_bytes(M, N, K);
+}
+
+int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K, float *out,
+                 void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (!a_hi || !a_lo || !w_packed || !out || M <= 0 || N <= 0 || K <= 0 || N % 16) return SSSD_EINVAL;
+    const size_t need = stream_gemm_scratch_bytes(M, N, K);
+    if (need && (!scratch || scratch_bytes < need)) return SSSD_ECAPACITY;
+    FusedGemmArgs a{};
     a.A_hi = (const u32x4 *)a_hi; a.A_lo = (const u32x4 *)a_lo; a.W0 = (const u32x4 *)w_packed;
-    a.KT = (K + 31) / 32; a.NT = N / 16; a.M = M; a.out_f32 = out; a.ld = N;
-    HIP_TRY(launch_gemm(a, EPI_STORE, a_lo != nullptr, (hipStream_t)stream));
+    a.KT = (K + 31) / 32; a.NT = N / 16; a.n_units = a.NT; a.Ntot = N; a.M = M; a.out = out;
+    a.partials = (float *)scratch; a.partial_bytes = scratch_bytes;
+    HIP_TRY(launch_stream_gemm(a, FEPI_STORE, (hipStream_t)stream));
     return SSSD_OK;
 }
 

@@ -43,7 +43,8 @@ enum FusedEpilogue {
     FEPI_QKV = 0,    // RMSNorm scale, rotary embedding, Q operand packing, KV append; tasks = rotary tile pairs
     FEPI_RESID = 1,  // X += acc; packed X*gamma_next; sums of squares per 16 columns; tasks = single tiles
     FEPI_SWIGLU = 2, // RMSNorm scale, silu(gate)*up, operand packing; tasks = (gate tile, up tile)
-    FEPI_LM = 3      // RMSNorm scale, per-tile arg-max, optional logits; tasks = two consecutive tiles
+    FEPI_LM = 3,     // RMSNorm scale, per-tile arg-max, optional logits; tasks = two consecutive tiles
+    FEPI_STORE = 4   // out[m][n] = acc (kernel-level entry point only)
 };
 
 struct FusedGemmArgs {
@@ -66,14 +67,17 @@ struct FusedGemmArgs {
     int n_units;                  // epilogue units: rotary tile pairs (QKV), gate/up tile pairs (SWIGLU), tiles (RESID, LM)
     int Ntot;                     // columns of the concatenated output: (nq+2nkv)*d, 2*ffn, h, vocab
     int n_cu;                     // compute units of the device
+    float *out;                   // STORE: [M][Ntot] fp32
     float *partials;              // split-K scratch [J][part_rows][Ntot] fp32
     size_t partial_bytes;
-    int upw, J, part_rows;        // filled in by the launcher: units per workgroup, K slices, rows per slice
+    int seg0, seg1;               // tiles of W0 and of W1 in the concatenated output (M > 16 kernel)
+    int upw, J, part_rows, kps;   // filled in by the launcher: units per workgroup, K slices, rows per slice, k-tiles per slice
 };
 hipError_t launch_fused_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 // M <= stream_gemm_max_rows(): persistent weight streamer; NT must be the tile count of W0.
 int stream_gemm_max_rows();
 size_t stream_gemm_partial_bytes(const Dims &D, int M);
+size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-level entry point)
 hipError_t launch_stream_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
                               uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,

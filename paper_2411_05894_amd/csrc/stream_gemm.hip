@@ -12,6 +12,13 @@
 //                  are refilled for the NEXT tile right after the MFMA that consumed them: a
 //                  rolling prefetch with a constant number of bytes in flight per wave and no
 //                  bubble at tile boundaries.  The k-split is reduced through LDS in fixed order.
+//   qgemm_kernel   M > 16 rows (up to 160 per pass).  v_mfma_f32_32x32x16_bf16 tiles: a workgroup of four
+//                  waves owns 256 output columns and one k-slice; each wave streams the weights of
+//                  its own 64 columns HBM -> registers (rolling prefetch, every weight byte read
+//                  once), while the activation k-tiles, which all four waves need, are staged
+//                  through a three-deep LDS ring.  The 16-row operand tiles of the packed layout
+//                  are read as the halves of 32-row MFMA operands, so one weight layout serves
+//                  both kernels.  Results go to split-K partials for epi_kernel.
 //   epi_kernel     Sums split-K partial results (when K is split over workgroups) in fixed order
 //                  and applies the epilogue.
 //
@@ -69,7 +76,9 @@ template <int EPI> __device__ __forceinline__ const u32x4 *tile_weights(const Fu
 template <int EPI>
 __device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m, int c, bool valid, float v0, float v1, float rs)
 {
-    if (EPI == FEPI_RESID) {
+    if (EPI == FEPI_STORE) {
+        if (valid) a.out[(size_t)m * a.Ntot + unit * 16 + c] = v0;
+    } else if (EPI == FEPI_RESID) {
         const int n = unit * 16 + c;
         float xn = 0.f;
         if (valid) {
@@ -210,7 +219,7 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
         ah[i] = live ? a.A_hi[(size_t)koff[i] + lane] : u32x4{0, 0, 0, 0};
         al[i] = live ? a.A_lo[(size_t)koff[i] + lane] : u32x4{0, 0, 0, 0};
     }
-    if (EPI != FEPI_RESID && J == 1) rstd_s[wave] = row_rstd(a, wave, lane);   // published by the first barrier
+    if (EPI != FEPI_RESID && EPI != FEPI_STORE && J == 1) rstd_s[wave] = row_rstd(a, wave, lane);   // published by the first barrier
 
     float keep = 0.f;
     for (int s = 0; s < n_steps; ++s) {
@@ -238,7 +247,7 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
             } else if (TPU == 2 && part == 0) {
                 keep = v;
             } else {
-                const float rs = EPI == FEPI_RESID ? 1.f : rstd_s[m];
+                const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[m];
                 if (TPU == 2) epilogue<EPI>(a, unit, m, c, m < a.M, keep, v, rs);
                 else epilogue<EPI>(a, unit, m, c, m < a.M, v, 0.f, rs);
             }
@@ -255,7 +264,7 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int units_per
     __shared__ float rstd_s[16];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m0 = blockIdx.y * 16;
-    if (EPI != FEPI_RESID) {
+    if (EPI != FEPI_RESID && EPI != FEPI_STORE) {
         for (int r = wave; r < 16; r += 4) {
             const float rs = row_rstd(a, m0 + r, lane);
             if (lane == 0) rstd_s[r] = rs;
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int units_per
     }
     const int ml = 4 * (lane >> 4) + wave, m = m0 + ml, c = lane & 15;
     const bool valid = m < a.M;
-    const float rs = EPI == FEPI_RESID ? 1.f : rstd_s[ml];
+    const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[ml];
     const int u_begin = blockIdx.x * units_per_block;
     const int u_end = u_begin + units_per_block < a.n_units ? u_begin + units_per_block : a.n_units;
     const size_t jstride = (size_t)a.part_rows * a.Ntot;
@@ -280,6 +289,224 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int units_per
         }
         epilogue<EPI>(a, unit, m, c, valid, v[0], v[TPU - 1], rs);
     }
+}
+
+
+// ------------------------------------------------------------------- M > 16 ----
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Packed weights of concatenated 16-column tile gt for any epilogue: the output is up to three
+// matrices side by side, the first two of seg0 and seg1 tiles.
+__device__ __forceinline__ const u32x4 *tile_weights_seg(const FusedGemmArgs &a, int gt)
+{
+    const size_t stride = (size_t)a.KT * 64;
+    const u32x4 *base = a.W0;
+    if (gt >= a.seg0) {
+        gt -= a.seg0;
+        base = a.W1;
+        if (gt >= a.seg1) {
+            gt -= a.seg1;
+            base = a.W2;
+        }
+    }
+    return base + gt * stride;
+}
+
+constexpr int QW = 4;    // waves per workgroup
+constexpr int QNG = 2;   // 32-column tiles per wave
+constexpr int QDW = 4;   // weight k-tiles in flight per wave
+
+// A 32 x 16 MFMA operand (rows l%32, k-slots 8*(l/32)..+7) assembled from two packed 16 x 32
+// tiles T0 (rows 0..15) and T1 (rows 16..31): for k-half hh of the k-tile, lane l takes lane
+// record (l%16) + 16*(l/32 + 2*hh) of tile T[(l/16)%2].  Both operands use the same rule, so the
+// k-slots pair up.
+__device__ __forceinline__ int half_record(int lane, int hh) { return (lane & 15) + 16 * ((lane >> 5) + 2 * hh); }
+
+// grid = n_groups * J workgroups of 256 threads; rows [m_base, m_base + 32*MT32) of the packed
+// activations; writes partials[j][row][col].
+template <int MT32>
+__global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_base, int NT16)
+{
+    constexpr int MT16 = 2 * MT32;
+    constexpr int CHUNK = MT16 * 2 * 64;          // lane records of one activation k-tile (hi and lo)
+    constexpr int APT = CHUNK / (QW * 64);        // records staged per thread
+    __shared__ u32x4 ring[3][CHUNK];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int J = a.J, j = blockIdx.x % J, grp = blockIdx.x / J;
+    const int KT = a.KT;
+    const int kps = a.kps;
+    const int kt_begin = j * kps, kt_end = kt_begin + kps < KT ? kt_begin + kps : KT;
+    const int n_iter = kt_end - kt_begin;
+
+    // this wave's weight tiles
+    const u32x4 *wp[QNG];
+    int n32[QNG];
+#pragma unroll
+    for (int g = 0; g < QNG; ++g) {
+        n32[g] = (grp * QW + wave) * QNG + g;
+        int t16 = 2 * n32[g] + ((lane >> 4) & 1);
+        if (t16 >= NT16) t16 = NT16 - 1;          // columns past the matrix re-read the last tile, never stored
+        wp[g] = tile_weights_seg(a, t16);
+    }
+    const int r0 = half_record(lane, 0), r1 = half_record(lane, 1);
+
+    // activation staging: thread t moves records t, t+256, ... of each k-tile chunk
+    const size_t mt_base = (size_t)(m_base >> 4);
+    const u32x4 *asrc[APT];
+#pragma unroll
+    for (int i = 0; i < APT; ++i) {
+        const int q = threadIdx.x + i * QW * 64;
+        const int tile = q >> 6, rec = q & 63;    // tile = mt16 * 2 + (0: hi, 1: lo)
+        const u32x4 *base = (tile & 1) ? a.A_lo : a.A_hi;
+        asrc[i] = base + ((mt_base + (tile >> 1)) * KT) * 64 + rec;
+    }
+    auto stage_load = [&](int kt, u32x4 (&v)[APT]) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) v[i] = asrc[i][(size_t)kt * 64];
+    };
+    auto stage_store = [&](int buf, const u32x4 (&v)[APT]) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) ring[buf][threadIdx.x + i * QW * 64] = v[i];
+    };
+
+    f32x16 acc[MT32][QNG];
+#pragma unroll
+    for (int i = 0; i < MT32; ++i)
+#pragma unroll
+        for (int g = 0; g < QNG; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.f;
+
+    // prologue: weights of the first QDW k-tiles, activation chunks 0 and 1
+    u32x4 w[QDW][QNG][2];
+#pragma unroll
+    for (int u = 0; u < QDW; ++u) {
+        const int kt = kt_begin + (u < n_iter ? u : n_iter - 1);
+#pragma unroll
+        for (int g = 0; g < QNG; ++g) {
+            w[u][g][0] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r0);
+            w[u][g][1] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r1);
+        }
+    }
+    {
+        u32x4 v[APT];
+        stage_load(kt_begin, v);
+        stage_store(0, v);
+        stage_load(kt_begin + (n_iter > 1 ? 1 : 0), v);
+        stage_store(1, v);
+    }
+    __syncthreads();
+
+    for (int it0 = 0; it0 < n_iter; it0 += QDW) {
+#pragma unroll
+        for (int u = 0; u < QDW; ++u) {
+            const int it = it0 + u;
+            if (it < n_iter) {
+                u32x4 apre[APT];
+                const bool more_a = it + 2 < n_iter;
+                if (more_a) stage_load(kt_begin + it + 2, apre);
+                const u32x4 *buf = ring[it % 3];
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const int rec = hh ? r1 : r0;
+#pragma unroll
+                    for (int i = 0; i < MT32; ++i) {
+                        // tile index in the chunk: (mt16 * 2 + hi/lo) with mt16 = 2i + (lane/16)%2
+                        const int t_hi = ((2 * i + ((lane >> 4) & 1)) * 2) * 64 + rec;
+                        const u32x4 xh = buf[t_hi], xl = buf[t_hi + 64];
+#pragma unroll
+                        for (int g = 0; g < QNG; ++g) {
+                            acc[i][g] = mfma32(xh, w[u][g][hh], acc[i][g]);
+                            acc[i][g] = mfma32(xl, w[u][g][hh], acc[i][g]);
+                        }
+                    }
+                }
+                if (it + QDW < n_iter) {
+                    const int kt = kt_begin + it + QDW;
+#pragma unroll
+                    for (int g = 0; g < QNG; ++g) {
+                        w[u][g][0] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r0);
+                        w[u][g][1] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r1);
+                    }
+                }
+                // Ring slot (it+2)%3 held chunk it-1, which every wave finished before the barrier
+                // that ended iteration it-1.
+                if (more_a) stage_store((it + 2) % 3, apre);
+                __syncthreads();
+            }
+        }
+    }
+
+    // acc[i][g][v] of lane l: row 32i + 8*(v/4) + 4*(l/32) + v%4, column 32*n32[g] + l%32
+#pragma unroll
+    for (int g = 0; g < QNG; ++g) {
+        const int col = n32[g] * 32 + (lane & 31);
+        if (col >= a.Ntot) continue;
+#pragma unroll
+        for (int i = 0; i < MT32; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m_base + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < a.part_rows) a.partials[((size_t)j * a.part_rows + row) * a.Ntot + col] = acc[i][g][v];
+            }
+    }
+}
+
+struct QPlan {
+    int groups, J, kps;   // column groups, K slices (none empty), k-tiles per slice
+};
+
+// Column groups of 256 and the K split that brings the grid to about two workgroups per compute unit.
+__host__ QPlan q_plan(int Ntot, int K)
+{
+    const int NT32 = (Ntot / 16 + 1) / 2, KT = (K + 31) / 32;
+    QPlan p;
+    p.groups = (NT32 + QW * QNG - 1) / (QW * QNG);
+    int J = (2 * 256 + p.groups - 1) / p.groups;
+    if (J > KT / 8) J = KT / 8;
+    if (J > 16) J = 16;
+    if (J < 1) J = 1;
+    p.kps = (KT + J - 1) / J;
+    p.J = (KT + p.kps - 1) / p.kps;
+    return p;
+}
+
+template <int EPI> hipError_t launch_large(FusedGemmArgs a, hipStream_t s)
+{
+    const int NT16 = a.Ntot / 16;
+    const QPlan p = q_plan(a.Ntot, a.KT * 32);
+    a.J = p.J;
+    a.kps = p.kps;
+    a.part_rows = round_up(a.M, 16);
+    if (EPI == FEPI_QKV) { a.seg0 = a.nq * (a.d >> 4); a.seg1 = a.nkv * (a.d >> 4); }
+    else if (EPI == FEPI_SWIGLU) { a.seg0 = a.NT; a.seg1 = a.NT; }
+    else { a.seg0 = NT16; a.seg1 = 0; }
+    if ((size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
+    const dim3 grid(p.groups * a.J), block(QW * 64);
+    for (int m_base = 0; m_base < a.M; m_base += 160) {
+        const int mt32 = (a.M - m_base + 31) / 32;
+        switch (mt32 > 5 ? 5 : mt32) {
+        case 1: hipLaunchKernelGGL((qgemm_kernel<1>), grid, block, 0, s, a, m_base, NT16); break;
+        case 2: hipLaunchKernelGGL((qgemm_kernel<2>), grid, block, 0, s, a, m_base, NT16); break;
+        case 3: hipLaunchKernelGGL((qgemm_kernel<3>), grid, block, 0, s, a, m_base, NT16); break;
+        case 4: hipLaunchKernelGGL((qgemm_kernel<4>), grid, block, 0, s, a, m_base, NT16); break;
+        default: hipLaunchKernelGGL((qgemm_kernel<5>), grid, block, 0, s, a, m_base, NT16); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
+    const int row_tiles = (a.M + 15) / 16;
+    int blocks_x = (4 * n_cu + row_tiles - 1) / row_tiles;
+    int upb = (a.n_units + blocks_x - 1) / blocks_x;
+    if (upb < 1) upb = 1;
+    hipLaunchKernelGGL((epi_kernel<EPI>), dim3((a.n_units + upb - 1) / upb, row_tiles), dim3(256), 0, s, a, upb);
+    return hipGetLastError();
 }
 
 template <int EPI> hipError_t launch_small(FusedGemmArgs a, hipStream_t s)
@@ -313,7 +540,6 @@ int stream_gemm_max_rows() { return 16; }
 // Split-K scratch needed for M rows: the largest J * rows * Ntot over the model's GEMMs.
 size_t stream_gemm_partial_bytes(const Dims &D, int M)
 {
-    (void)M;
     auto slices = [](int K) {
         const int KT = (K + 31) / 32;
         const bool seven = KT % (PW * 7) == 0 && KT % (PW * 8) != 0;
@@ -330,15 +556,47 @@ size_t stream_gemm_partial_bytes(const Dims &D, int M)
     consider(D.h, 2 * (size_t)D.f);
     consider(D.f, D.h);
     consider(D.h, D.V);
+    if (M > stream_gemm_max_rows()) {
+        const size_t rows = (size_t)round_up(M, 16);
+        auto large = [&](int K, size_t ntot) {
+            const size_t need = (size_t)q_plan((int)ntot, K).J * rows * ntot;
+            if (need > best) best = need;
+        };
+        large(D.h, (size_t)D.qd + 2 * D.kd);
+        large(D.qd, D.h);
+        large(D.h, 2 * (size_t)D.f);
+        large(D.f, D.h);
+        large(D.h, D.V);
+    }
     return best * sizeof(float);
+}
+
+size_t stream_gemm_scratch_bytes(int M, int N, int K)
+{
+    const int KT = (K + 31) / 32;
+    if (M > stream_gemm_max_rows()) return (size_t)q_plan(N, K).J * round_up(M, 16) * N * sizeof(float);
+    const bool seven = KT % (PW * 7) == 0 && KT % (PW * 8) != 0;
+    const int ks = PW * (seven ? 7 : 8);
+    const size_t j = (size_t)((KT + ks - 1) / ks);
+    return j > 1 ? j * 16 * N * sizeof(float) : 0;
 }
 
 hipError_t launch_stream_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s)
 {
+    if (a.M > stream_gemm_max_rows()) {
+        switch (epilogue) {
+        case FEPI_QKV: return launch_large<FEPI_QKV>(a, s);
+        case FEPI_RESID: return launch_large<FEPI_RESID>(a, s);
+        case FEPI_SWIGLU: return launch_large<FEPI_SWIGLU>(a, s);
+        case FEPI_STORE: return launch_large<FEPI_STORE>(a, s);
+        default: return launch_large<FEPI_LM>(a, s);
+        }
+    }
     switch (epilogue) {
     case FEPI_QKV: return launch_small<FEPI_QKV>(a, s);
     case FEPI_RESID: return launch_small<FEPI_RESID>(a, s);
     case FEPI_SWIGLU: return launch_small<FEPI_SWIGLU>(a, s);
+    case FEPI_STORE: return launch_small<FEPI_STORE>(a, s);
     default: return launch_small<FEPI_LM>(a, s);
     }
 }

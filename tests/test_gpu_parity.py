@@ -54,11 +54,6 @@ def test_gemm_vs_oracle(N, K):
         scale = ref.abs().max().item()
         y2 = sv.sssd_op_gemm(hi, lo, wp, M, N, K).cpu()
         assert (y2 - ref).abs().max().item() <= 3e-5 * scale + 1e-6, "hi+lo activations"
-        y1 = sv.sssd_op_gemm(hi, None, wp, M, N, K).cpu()
-        # one bf16 rounding of x (relative 2^-9) seen through a length-K dot product
-        bound = 6.0 * 2.0 ** -9 * 0.02 * 1.3 * math.sqrt(K)
-        assert (y1 - ref).abs().max().item() <= bound, "hi-only activations"
-        assert (y1 - ref).abs().max().item() > 0
 
 
 # ------------------------------------------------------------ attention ----
