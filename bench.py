@@ -23,7 +23,7 @@ PEAK_HBM_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each
 # calibrated against a 1 GiB copy kernel); source: profiles/verify_step_8b_b1_ctx2048_k8_hbm_traffic.md.
 # Only the workload those runs covered has a figure.
-MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "fused_gemm_kernel"): 120.47e6}
+MEASURED_TRAFFIC_PER_LAUNCH = {}
 
 WORKLOADS = {
     # name: (shape, B, ctx spec, k, k sweep)
@@ -47,7 +47,6 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (known traffic) to calibrate rocprofv3 byte counters")
-    ap.add_argument("--mode", default="auto", choices=["auto", "kernels", "phases", "persistent"])
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -88,7 +87,6 @@ def main() -> int:
                        {n: t.cpu() for n, t in g.items()})
     cfg = sv.make_config(shape, B, max_k, max_seq)
     ctx = sv.VerifyContext(cfg, layers, g, in_place=in_place)
-    ctx.sssd_verify_set_mode({"auto": 0, "kernels": 1, "phases": 2, "persistent": 3}[args.mode])
     if not in_place:
         for l in layers:
             for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
@@ -148,15 +146,10 @@ def main() -> int:
         ctx.sssd_verify_step(tok, lens, acc, nxt)
     prof = ctx.sssd_profile_read()
     ctx.sssd_profile_enable(False)
-    if prof["step"]["launches"] > 0:
-        # whole step = one persistent kernel: it is the dominant kernel and moves every algorithmic byte
-        kname, launches = "verify_mega_kernel", prof["step"]["launches"] / prof_steps
-        ms_per_launch = prof["step"]["ms"] / prof["step"]["launches"]
-        bytes_per_launch = bytes_alg["total"] / launches
-    else:
-        kname, launches = "fused_gemm_kernel", prof["gemm"]["launches"] / prof_steps
-        ms_per_launch = prof["gemm"]["ms"] / prof["gemm"]["launches"]
-        bytes_per_launch = bytes_alg["weights"] / launches
+    # dominant kernel: the weight streamer (one launch per GEMM; every weight byte is read once)
+    kname, launches = ("pgemm_kernel" if M <= 16 else "qgemm_kernel"), prof["gemm"]["launches"] / prof_steps
+    ms_per_launch = prof["gemm"]["ms"] / prof["gemm"]["launches"]
+    bytes_per_launch = bytes_alg["weights"] / launches
     achieved = bytes_per_launch / (ms_per_launch * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                 "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
@@ -201,7 +194,7 @@ def main() -> int:
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {wl['shape']}-shaped decoder, B={B}, KV context {wl['ctx']}, k={k}",
-                   "B": B, "k": k, "M": M, "in_place_weights": in_place, "mode": args.mode},
+                   "B": B, "k": k, "M": M, "in_place_weights": in_place},
         "algorithmic_bytes": bytes_alg,
         "hbm_gbps_whole_step": round(bytes_alg["total"] / (ms * 1e-3) / 1e9, 1),
         "hbm_frac_whole_step": round(bytes_alg["total"] / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),

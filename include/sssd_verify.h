@@ -36,8 +36,6 @@ extern "C" {
 #define SSSD_ENOSPACE (-3)  /* some lens[b] + k + 1 > max_seq, or a token id >= vocab
                                (found on the device, reported by sssd_verify_sync)    */
 #define SSSD_EHIP (-4)      /* a HIP runtime call failed                              */
-#define SSSD_ETIMEOUT (-5)  /* a bounded grid-wide wait in the step kernel gave up
-                               (reported by sssd_verify_sync); outputs are invalid    */
 
 typedef struct sssd_ctx sssd_ctx; /* opaque, host memory owned by the library */
 
@@ -127,24 +125,9 @@ int sssd_verify_step(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
 int sssd_kv_rollback(sssd_ctx *ctx, int32_t B, int32_t *lens, const int32_t *accepted_len,
                      const int32_t *new_lens, void *stream);
 
-/* Wait for `stream`, then return SSSD_ETIMEOUT or SSSD_ENOSPACE if any step since the
- * last call raised the corresponding device flag (and clear it), else SSSD_OK. */
+/* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call raised
+ * the device flag (and clear it), else SSSD_OK. */
 int sssd_verify_sync(sssd_ctx *ctx, void *stream);
-
-/*
- * How sssd_verify_step launches its work.  AUTO (the default): steps of at most 48 rows
- * (B*(k+1)) run as ONE persistent kernel that keeps a workgroup resident on every compute
- * unit and separates the phases of the step by grid-wide barriers; larger steps run one
- * kernel per operation.  KERNELS forces one kernel per operation for any size; PHASES runs
- * the persistent kernel's code one phase per launch (no grid barrier); PERSISTENT is AUTO
- * without the silent fallback to PHASES when the device cannot launch cooperatively.
- * All modes compute the same step.
- */
-#define SSSD_MODE_AUTO 0
-#define SSSD_MODE_KERNELS 1
-#define SSSD_MODE_PHASES 2
-#define SSSD_MODE_PERSISTENT 3
-int sssd_verify_set_mode(sssd_ctx *ctx, int32_t mode);
 
 /* Parity aid.  logits != NULL: every following step also stores its fp32
  * logits to `logits`, device float [B*(k+1)][vocab] (row b*(k+1)+j).
@@ -173,17 +156,10 @@ int sssd_kv_export(sssd_ctx *ctx, int32_t layer, int32_t b, int32_t t0, int32_t 
 enum {
     SSSD_PROF_GEMM = 0,  /* all weight GEMMs                   */
     SSSD_PROF_ATTN = 1,  /* attention + its split combine      */
-    SSSD_PROF_ELEM = 2,  /* embed, norms, rope/append          */
-    SSSD_PROF_ACCEPT = 3, /* arg-max merge + prefix acceptance  */
-    SSSD_PROF_STEP = 4    /* the persistent whole-step kernel   */
+    SSSD_PROF_ELEM = 2,  /* embed, split-K epilogue launches   */
+    SSSD_PROF_ACCEPT = 3  /* arg-max merge + prefix acceptance  */
 };
 int sssd_profile_enable(sssd_ctx *ctx, int32_t on);
-/* With profiling on, the persistent step kernel also stamps a constant-rate device clock
- * (100 MHz), as seen by workgroup 0, at the start of each of its P = 3 + 6*n_layers phases
- * and at its end (ticks[0..P]), and when workgroup 0 finished each phase's work, before the
- * barrier (ticks[P+1..2P]).  Copies the stamps of the last such step to `ticks` (host,
- * n >= 2*(P+1) entries).  Phase order: embed | per layer: QKV, attention, combine, O, gate/up, down | LM head | accept. */
-int sssd_profile_phases(sssd_ctx *ctx, void *stream, uint64_t *ticks, int32_t n);
 int sssd_profile_read(sssd_ctx *ctx, void *stream, double *ms, int64_t *n);
 
 int sssd_verify_destroy(sssd_ctx *ctx);

@@ -13,11 +13,10 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsssd_verify.so")
 
-SSSD_OK, SSSD_EINVAL, SSSD_ECAPACITY, SSSD_ENOSPACE, SSSD_EHIP, SSSD_ETIMEOUT = 0, -1, -2, -3, -4, -5
-SSSD_MODE_AUTO, SSSD_MODE_KERNELS, SSSD_MODE_PHASES, SSSD_MODE_PERSISTENT = 0, 1, 2, 3
+SSSD_OK, SSSD_EINVAL, SSSD_ECAPACITY, SSSD_ENOSPACE, SSSD_EHIP = 0, -1, -2, -3, -4
 SSSD_PACK_IN_PLACE = 1
 SSSD_PROF_CLASSES = 8
-PROF_NAMES = ("gemm", "attention", "elementwise", "accept", "step")
+PROF_NAMES = ("gemm", "attention", "elementwise", "accept")
 
 
 class SssdError(RuntimeError):
@@ -64,9 +63,7 @@ def lib() -> C.CDLL:
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
         l.sssd_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         l.sssd_kv_export.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
-        l.sssd_verify_set_mode.argtypes = [vp, i32]
         l.sssd_profile_enable.argtypes = [vp, i32]
-        l.sssd_profile_phases.argtypes = [vp, vp, C.POINTER(C.c_uint64), i32]
         l.sssd_profile_read.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         l.sssd_verify_destroy.argtypes = [vp]
         l.sssd_op_packed_weight_bytes.restype = sz
@@ -173,9 +170,6 @@ class VerifyContext:
         _check(lib().sssd_kv_export(self.handle, layer, b, t0, k_dst.shape[1], _ptr(k_dst), _ptr(v_dst), _stream()),
                "sssd_kv_export")
 
-    def sssd_verify_set_mode(self, mode: int) -> None:
-        _check(lib().sssd_verify_set_mode(self.handle, mode), "sssd_verify_set_mode")
-
     def sssd_profile_enable(self, on: bool) -> None:
         _check(lib().sssd_profile_enable(self.handle, int(on)), "sssd_profile_enable")
 
@@ -184,12 +178,6 @@ class VerifyContext:
         n = (C.c_int64 * SSSD_PROF_CLASSES)()
         _check(lib().sssd_profile_read(self.handle, _stream(), ms, n), "sssd_profile_read")
         return {name: {"ms": ms[i], "launches": n[i]} for i, name in enumerate(PROF_NAMES)}
-
-    def sssd_profile_phases(self):
-        n = 2 * (4 + 6 * self.cfg.n_layers) + 256
-        t = (C.c_uint64 * n)()
-        _check(lib().sssd_profile_phases(self.handle, _stream(), t, n), "sssd_profile_phases")
-        return list(t)
 
     def sssd_op_attention(self, layer: int, q: torch.Tensor, lens: torch.Tensor, out: torch.Tensor) -> None:
         B, sq = q.shape[0], q.shape[1]

@@ -11,21 +11,19 @@ namespace {
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
-typedef LayerPtrs LayerW;
+struct LayerW {
+    const uint16_t *wq, *wk, *wv, *wo, *wg, *wu, *wd;  // packed
+    const uint16_t *attn_norm, *mlp_norm;
+};
 
 struct Buffers {
-    float *X, *qkv;
+    float *X;
     uint16_t *Ah_hi, *Ah_lo, *Aq_hi, *Aq_lo, *Af_hi, *Af_lo;
     uint16_t *Qp, *Qp_lo;
     float *part_o, *part_ml, *part_val;
     int *part_idx;
     int32_t *pos_base, *err_flag, *that_dbg;
-    float *rope_cs, *ssq, *ssq1;
-    unsigned *bar;
-    LayerPtrs *layer_tab;
-    unsigned long long *tstamps;
-    uint16_t *mega_A[4];
-    size_t mega_stride[4], mega_half[4];
+    float *rope_cs, *ssq1;
     uint8_t *staging;
     size_t staging_bytes;
     float *partials;
@@ -60,8 +58,6 @@ struct sssd_ctx {
     double prof_ms[SSSD_PROF_CLASSES];
     int64_t prof_n[SSSD_PROF_CLASSES];
     int device, n_cu;
-    int mode;       // SSSD_MODE_*
-    bool coop_ok;
 };
 
 namespace {
@@ -120,7 +116,6 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     const size_t NTv = D.V / 16;
     Buffers b{};
     b.X = (float *)take((size_t)S.m_alloc * D.h * 4);
-    b.qkv = (float *)take((size_t)S.m_alloc * (D.qd + 2 * D.kd) * 4);
     b.Ah_hi = (uint16_t *)take(S.tiles_alloc * KTh * 1024);
     b.Ah_lo = (uint16_t *)take(S.tiles_alloc * KTh * 1024);
     b.Aq_hi = (uint16_t *)take(S.tiles_alloc * KTq * 1024);
@@ -136,21 +131,7 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.part_idx = (int *)take((size_t)S.m_alloc * NTv * 4);
     b.pos_base = (int32_t *)take((size_t)D.max_batch * 4);
     b.err_flag = (int32_t *)take(4);
-    b.bar = (unsigned *)take(8);
     b.ssq1 = (float *)take((size_t)S.m_alloc * (D.h / 16) * 4);
-    b.ssq = (float *)take((size_t)(2 * D.L + 1) * 48 * (D.h / 16) * 4);
-    {
-        // versioned operand buffers of the persistent kernel: 3 row tiles, one copy per (layer, role)
-        const size_t kt[4] = {KTh, KTq, KTh, KTf};
-        const size_t versions[4] = {(size_t)D.L + 1, (size_t)D.L, (size_t)D.L, (size_t)D.L};
-        for (int i = 0; i < 4; ++i) {
-            b.mega_half[i] = 3 * kt[i] * 512;
-            b.mega_stride[i] = 2 * b.mega_half[i];
-            b.mega_A[i] = (uint16_t *)take(versions[i] * b.mega_stride[i] * 2);
-        }
-    }
-    b.layer_tab = (LayerPtrs *)take((size_t)D.L * sizeof(LayerPtrs));
-    b.tstamps = (unsigned long long *)take((size_t)(4 + 6 * D.L) * 2 * 8 + 256 * 8);
     b.that_dbg = (int32_t *)take((size_t)S.m_alloc * 4);
     b.rope_cs = (float *)take((size_t)D.max_seq * (D.d / 2) * 2 * 4);
     b.staging_bytes = (size_t)64 << 20;
@@ -247,7 +228,6 @@ const char *sssd_strerror(int code)
     case SSSD_ECAPACITY: return "capacity exceeded (batch, draft count or buffer size)";
     case SSSD_ENOSPACE: return "a sequence does not fit its KV rows, or a token id is out of range";
     case SSSD_EHIP: return "HIP runtime error";
-    case SSSD_ETIMEOUT: return "a grid-wide wait inside the step kernel gave up; the step's outputs are invalid";
     default: return "unknown error";
     }
 }
@@ -365,13 +345,10 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
         lw.mlp_norm = (const uint16_t *)w->mlp_norm[l];
     }
     INIT_RC(place(w->lm_head, D.V, D.h, &c->lm_head));
-    INIT_TRY(hipMemcpyAsync(c->W.layer_tab, c->layers.data(), (size_t)D.L * sizeof(LayerPtrs), hipMemcpyHostToDevice, s));
     {
         hipDeviceProp_t prop;
         INIT_TRY(hipGetDeviceProperties(&prop, c->device));
         c->n_cu = prop.multiProcessorCount;
-        c->coop_ok = prop.cooperativeLaunch != 0;
-        c->mode = SSSD_MODE_AUTO;
     }
     INIT_TRY(hipStreamSynchronize(s));
     c->magic = MAGIC;
@@ -409,157 +386,72 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
     hipStream_t s = (hipStream_t)stream;
     Buffers &W = c->W;
     const int M = B * (k + 1);
-    // hi+lo activations: errors of single-bf16 activations are amplified ~30x through 32 layers
-    // of the benchmark's random-weight models and would miss the 2e-2 logit tolerance.
-    const bool split = true;
     StepIO io{tokens, lens, accepted_len, next_token, B, k};
 
-    auto gemm = [&](const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W0, const uint16_t *W1, int N, int K,
-                    int epi, float *out, int ld, uint16_t *ohi, uint16_t *olo, int KT_out) -> hipError_t {
-        GemmArgs a{};
-        a.A_hi = (const u32x4 *)Ahi; a.A_lo = (const u32x4 *)Alo;
-        a.W0 = (const u32x4 *)W0; a.W1 = (const u32x4 *)W1;
-        a.KT = (K + 31) / 32; a.NT = N / 16; a.M = M;
-        a.out_f32 = out; a.ld = ld; a.out_hi = ohi; a.out_lo = olo; a.KT_out = KT_out;
-        a.logits = c->dbg_logits; a.part_val = W.part_val; a.part_idx = W.part_idx;
-        Prof p(c, s, SSSD_PROF_GEMM);
-        return launch_gemm(a, epi, split, s);
-    };
-
-    if (c->mode == SSSD_MODE_AUTO) {
-        // Six fused launches per layer (QKV, attention, merge, O, gate/up, down).
-        {
-            Prof p(c, s, SSSD_PROF_ELEM);
-            HIP_TRY(launch_fused_embed(D, io, c->embed, c->layers[0].attn_norm, W.X, W.Ah_hi, W.Ah_lo, W.ssq1, W.pos_base,
-                                       W.err_flag, s));
-        }
-        FusedGemmArgs f{};
-        f.M = M; f.h = D.h; f.d = D.d; f.nq = D.nq; f.nkv = D.nkv; f.seq_pad = D.seq_pad; f.k = k;
-        f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps;
-        f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
-        f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
-        const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
-        f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
-        const bool streamer = true;
-        auto fgemm = [&](int epi) -> hipError_t {
-            Prof p(c, s, SSSD_PROF_GEMM);
-            return streamer ? launch_stream_gemm(f, epi, s) : launch_fused_gemm(f, epi, s);
-        };
-        for (int l = 0; l < D.L; ++l) {
-            const LayerW &lw = c->layers[l];
-            uint16_t *Kl = c->Kc + (size_t)l * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)l * c->S.kv_layer_elems;
-            // QKV
-            f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
-            f.W0 = (const u32x4 *)lw.wq; f.W1 = (const u32x4 *)lw.wk; f.W2 = (const u32x4 *)lw.wv;
-            f.n_tasks = (D.nq + 2 * D.nkv) * (D.d / 32); f.NT = D.qd / 16; f.Kc = Kl; f.Vc = Vl;
-            f.n_units = f.n_tasks; f.Ntot = D.qd + 2 * D.kd;
-            HIP_TRY(fgemm(FEPI_QKV));
-            {
-                AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
-                Prof p(c, s, SSSD_PROF_ATTN);
-                HIP_TRY(launch_attention(D, a, s));
-            }
-            // O
-            f.A_hi = (const u32x4 *)W.Aq_hi; f.A_lo = (const u32x4 *)W.Aq_lo; f.KT = KTq;
-            f.W0 = (const u32x4 *)lw.wo; f.NT = D.h / 16; f.n_tasks = f.NT; f.gamma_next = lw.mlp_norm;
-            f.n_units = f.NT; f.Ntot = D.h;
-            f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
-            HIP_TRY(fgemm(FEPI_RESID));
-            // gate/up
-            f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
-            f.W0 = (const u32x4 *)lw.wg; f.W1 = (const u32x4 *)lw.wu; f.n_tasks = D.f / 16;
-            f.NT = D.f / 16; f.n_units = f.NT; f.Ntot = 2 * D.f;
-            f.out_hi = W.Af_hi; f.out_lo = W.Af_lo; f.KT_out = KTf;
-            HIP_TRY(fgemm(FEPI_SWIGLU));
-            // down
-            f.A_hi = (const u32x4 *)W.Af_hi; f.A_lo = (const u32x4 *)W.Af_lo; f.KT = KTf;
-            f.W0 = (const u32x4 *)lw.wd; f.NT = D.h / 16; f.n_tasks = f.NT;
-            f.n_units = f.NT; f.Ntot = D.h;
-            f.gamma_next = l + 1 < D.L ? c->layers[l + 1].attn_norm : c->final_norm;
-            f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
-            HIP_TRY(fgemm(FEPI_RESID));
-        }
-        if (c->dbg_hidden)
-            HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
-        f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
-        f.W0 = (const u32x4 *)c->lm_head; f.NT = D.V / 16; f.n_tasks = (f.NT + 1) / 2;
-        f.n_units = f.NT; f.Ntot = D.V;
-        HIP_TRY(fgemm(FEPI_LM));
-        {
-            Prof p(c, s, SSSD_PROF_ACCEPT);
-            HIP_TRY(launch_accept(D, io, W.part_val, W.part_idx, D.V / 16, W.that_dbg, s));
-        }
-        return SSSD_OK;
-    }
-    const bool want_mega = c->mode == SSSD_MODE_PHASES || c->mode == SSSD_MODE_PERSISTENT;
-    if (want_mega && M <= mega_max_rows()) {
-        MegaArgs a{};
-        a.D = D; a.io = io; a.layers = W.layer_tab;
-        a.embed = c->embed; a.lm_head = c->lm_head; a.final_norm = c->final_norm;
-        a.X = W.X; a.ssq = W.ssq;
-        for (int i = 0; i < 4; ++i) { a.A[i] = W.mega_A[i]; a.A_stride[i] = W.mega_stride[i]; a.A_half[i] = W.mega_half[i]; }
-        a.Qp = W.Qp; a.Qp_lo = W.Qp_lo; a.Kc = c->Kc; a.Vc = c->Vc;
-        a.part_o = W.part_o; a.part_ml = W.part_ml; a.part_val = W.part_val; a.part_idx = W.part_idx;
-        a.pos_base = W.pos_base; a.err_flag = W.err_flag; a.that_dbg = W.that_dbg; a.rope_cs = W.rope_cs;
-        a.bar = W.bar; a.dbg_logits = c->dbg_logits; a.dbg_hidden = c->dbg_hidden;
-        a.tstamps = c->prof_on ? W.tstamps : nullptr;
-        a.kv_layer_elems = c->S.kv_layer_elems; a.q_rows_pad = c->S.q_rows_pad;
-        const int n_phases = 3 + 6 * D.L;
-        int per_cu = 0;
-        bool persistent = c->mode != SSSD_MODE_PHASES && c->coop_ok;
-        if (persistent && (mega_occupancy(M, &per_cu) != hipSuccess || per_cu < 1)) persistent = false;
-        Prof p(c, s, SSSD_PROF_STEP);
-        if (persistent) {
-            HIP_TRY(hipMemsetAsync(W.bar, 0, 8, s));
-            a.phase_lo = 0; a.phase_hi = n_phases;
-            HIP_TRY(launch_mega(a, c->n_cu, true, s));
-        } else {
-            for (int ph = 0; ph < n_phases; ++ph) {
-                a.phase_lo = ph; a.phase_hi = ph + 1;
-                HIP_TRY(launch_mega(a, c->n_cu, false, s));
-            }
-        }
-        return SSSD_OK;
-    }
+    // Six launches per layer (QKV, attention, merge, O, gate/up, down) plus an epilogue launch
+    // after every GEMM whose K is split over workgroups.
     {
         Prof p(c, s, SSSD_PROF_ELEM);
-        HIP_TRY(launch_embed(D, io, c->embed, W.X, W.pos_base, W.err_flag, s));
+        HIP_TRY(launch_fused_embed(D, io, c->embed, c->layers[0].attn_norm, W.X, W.Ah_hi, W.Ah_lo, W.ssq1, W.pos_base,
+                                   W.err_flag, s));
     }
-    const int ldq = D.qd + 2 * D.kd;
+    FusedGemmArgs f{};
+    f.M = M; f.h = D.h; f.d = D.d; f.nq = D.nq; f.nkv = D.nkv; f.seq_pad = D.seq_pad; f.k = k;
+    f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps;
+    f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
+    f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
+    const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
+    f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
+    auto fgemm = [&](int epi) -> hipError_t {
+        bool more = false;
+        {
+            Prof p(c, s, SSSD_PROF_GEMM);
+            hipError_t e = launch_stream_gemm(f, epi, s, &more);
+            if (e != hipSuccess || !more) return e;
+        }
+        Prof p(c, s, SSSD_PROF_ELEM);
+        return launch_stream_epilogue(f, epi, s);
+    };
     for (int l = 0; l < D.L; ++l) {
         const LayerW &lw = c->layers[l];
-        {
-            Prof p(c, s, SSSD_PROF_ELEM);
-            HIP_TRY(launch_rmsnorm_pack(D, W.X, lw.attn_norm, M, W.Ah_hi, W.Ah_lo, s));
-        }
-        HIP_TRY(gemm(W.Ah_hi, W.Ah_lo, lw.wq, nullptr, D.qd, D.h, EPI_STORE, W.qkv, ldq, nullptr, nullptr, 0));
-        HIP_TRY(gemm(W.Ah_hi, W.Ah_lo, lw.wk, nullptr, D.kd, D.h, EPI_STORE, W.qkv + D.qd, ldq, nullptr, nullptr, 0));
-        HIP_TRY(gemm(W.Ah_hi, W.Ah_lo, lw.wv, nullptr, D.kd, D.h, EPI_STORE, W.qkv + D.qd + D.kd, ldq, nullptr, nullptr, 0));
         uint16_t *Kl = c->Kc + (size_t)l * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)l * c->S.kv_layer_elems;
-        {
-            Prof p(c, s, SSSD_PROF_ELEM);
-            HIP_TRY(launch_rope_append(D, W.qkv, W.pos_base, B, k, W.rope_cs, W.Qp, W.Qp_lo, Kl, Vl, s));
-        }
+        // QKV
+        f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
+        f.W0 = (const u32x4 *)lw.wq; f.W1 = (const u32x4 *)lw.wk; f.W2 = (const u32x4 *)lw.wv;
+        f.NT = D.qd / 16; f.Kc = Kl; f.Vc = Vl;
+        f.n_units = (D.nq + 2 * D.nkv) * (D.d / 32); f.Ntot = D.qd + 2 * D.kd;
+        HIP_TRY(fgemm(FEPI_QKV));
         {
             AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
             Prof p(c, s, SSSD_PROF_ATTN);
             HIP_TRY(launch_attention(D, a, s));
         }
-        HIP_TRY(gemm(W.Aq_hi, W.Aq_lo, lw.wo, nullptr, D.h, D.qd, EPI_RESID, W.X, D.h, nullptr, nullptr, 0));
-        {
-            Prof p(c, s, SSSD_PROF_ELEM);
-            HIP_TRY(launch_rmsnorm_pack(D, W.X, lw.mlp_norm, M, W.Ah_hi, W.Ah_lo, s));
-        }
-        HIP_TRY(gemm(W.Ah_hi, W.Ah_lo, lw.wg, lw.wu, D.f, D.h, EPI_SWIGLU, nullptr, 0, W.Af_hi, W.Af_lo, (D.f + 31) / 32));
-        HIP_TRY(gemm(W.Af_hi, W.Af_lo, lw.wd, nullptr, D.h, D.f, EPI_RESID, W.X, D.h, nullptr, nullptr, 0));
+        // O
+        f.A_hi = (const u32x4 *)W.Aq_hi; f.A_lo = (const u32x4 *)W.Aq_lo; f.KT = KTq;
+        f.W0 = (const u32x4 *)lw.wo; f.NT = D.h / 16; f.gamma_next = lw.mlp_norm;
+        f.n_units = f.NT; f.Ntot = D.h;
+        f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
+        HIP_TRY(fgemm(FEPI_RESID));
+        // gate/up
+        f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
+        f.W0 = (const u32x4 *)lw.wg; f.W1 = (const u32x4 *)lw.wu;
+        f.NT = D.f / 16; f.n_units = f.NT; f.Ntot = 2 * D.f;
+        f.out_hi = W.Af_hi; f.out_lo = W.Af_lo; f.KT_out = KTf;
+        HIP_TRY(fgemm(FEPI_SWIGLU));
+        // down
+        f.A_hi = (const u32x4 *)W.Af_hi; f.A_lo = (const u32x4 *)W.Af_lo; f.KT = KTf;
+        f.W0 = (const u32x4 *)lw.wd; f.NT = D.h / 16;
+        f.n_units = f.NT; f.Ntot = D.h;
+        f.gamma_next = l + 1 < D.L ? c->layers[l + 1].attn_norm : c->final_norm;
+        f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
+        HIP_TRY(fgemm(FEPI_RESID));
     }
     if (c->dbg_hidden)
         HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
-    {
-        Prof p(c, s, SSSD_PROF_ELEM);
-        HIP_TRY(launch_rmsnorm_pack(D, W.X, c->final_norm, M, W.Ah_hi, W.Ah_lo, s));
-    }
-    HIP_TRY(gemm(W.Ah_hi, W.Ah_lo, c->lm_head, nullptr, D.V, D.h, EPI_LMHEAD, nullptr, D.V, nullptr, nullptr, 0));
+    f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
+    f.W0 = (const u32x4 *)c->lm_head; f.NT = D.V / 16;
+    f.n_units = f.NT; f.Ntot = D.V;
+    HIP_TRY(fgemm(FEPI_LM));
     {
         Prof p(c, s, SSSD_PROF_ACCEPT);
         HIP_TRY(launch_accept(D, io, W.part_val, W.part_idx, D.V / 16, W.that_dbg, s));
@@ -582,15 +474,8 @@ int sssd_verify_sync(sssd_ctx *c, void *stream)
     if (!valid(c)) return SSSD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     int32_t flag = 0;
-    unsigned bar[2] = {0, 0};
     HIP_TRY(hipMemcpyAsync(&flag, c->W.err_flag, 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(bar, c->W.bar, 8, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    if (bar[1]) {
-        HIP_TRY(hipMemsetAsync(c->W.bar, 0, 8, s));
-        HIP_TRY(hipStreamSynchronize(s));
-        return SSSD_ETIMEOUT;
-    }
     if (flag) {
         HIP_TRY(hipMemsetAsync(c->W.err_flag, 0, 4, s));
         HIP_TRY(hipStreamSynchronize(s));
@@ -624,28 +509,12 @@ int sssd_kv_export(sssd_ctx *c, int32_t layer, int32_t b, int32_t t0, int32_t n_
     return kv_copy(c, layer, b, t0, n_rows, k_dst, v_dst, false, stream);
 }
 
-int sssd_verify_set_mode(sssd_ctx *c, int32_t mode)
-{
-    if (!valid(c) || mode < SSSD_MODE_AUTO || mode > SSSD_MODE_PERSISTENT) return SSSD_EINVAL;
-    c->mode = mode;
-    return SSSD_OK;
-}
-
 int sssd_profile_enable(sssd_ctx *c, int32_t on)
 {
     if (!valid(c)) return SSSD_EINVAL;
     c->prof_on = on != 0;
     c->prof_used = 0;
     for (int i = 0; i < SSSD_PROF_CLASSES; ++i) { c->prof_ms[i] = 0; c->prof_n[i] = 0; }
-    return SSSD_OK;
-}
-
-int sssd_profile_phases(sssd_ctx *c, void *stream, uint64_t *ticks, int32_t n)
-{
-    if (!valid(c) || !ticks || n < 2 * (4 + 6 * c->D.L)) return SSSD_EINVAL;
-    hipStream_t s = (hipStream_t)stream;
-    HIP_TRY(hipMemcpyAsync(ticks, c->W.tstamps, (size_t)(n < 2 * (4 + 6 * c->D.L) + 256 ? 2 * (4 + 6 * c->D.L) : 2 * (4 + 6 * c->D.L) + 256) * 8, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
     return SSSD_OK;
 }
 
@@ -708,7 +577,9 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
     a.A_hi = (const u32x4 *)a_hi; a.A_lo = (const u32x4 *)a_lo; a.W0 = (const u32x4 *)w_packed;
     a.KT = (K + 31) / 32; a.NT = N / 16; a.n_units = a.NT; a.Ntot = N; a.M = M; a.out = out;
     a.partials = (float *)scratch; a.partial_bytes = scratch_bytes;
-    HIP_TRY(launch_stream_gemm(a, FEPI_STORE, (hipStream_t)stream));
+    bool more = false;
+    HIP_TRY(launch_stream_gemm(a, FEPI_STORE, (hipStream_t)stream, &more));
+    if (more) HIP_TRY(launch_stream_epilogue(a, FEPI_STORE, (hipStream_t)stream));
     return SSSD_OK;
 }
 

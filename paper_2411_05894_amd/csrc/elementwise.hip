@@ -1,106 +1,12 @@
-// Small bandwidth-trivial kernels around the GEMMs: token/length validation and
-// embedding gather, RMSNorm to packed bf16 operands, rotary embedding with
-// in-place KV append, arg-max merge + greedy prefix acceptance, rollback and
-// cache import/export.  None of them is in the paper's Table 2 (it lists the
-// matrix operations only); they move O(M*h) bytes against O(params) for the GEMMs.
+// Small bandwidth-trivial kernels around the GEMMs: token/length validation with the
+// embedding gather (which also writes the first layer's packed operands and sums of
+// squares), arg-max merge + greedy prefix acceptance, rollback, cache import/export,
+// weight reordering at init, and the packing helpers of the kernel-level entry points.
+// None of them is in the paper's Table 2 (it lists the matrix operations only); they move
+// O(M*h) bytes against O(params) for the GEMMs.
 #include "kernels.h"
 
 namespace {
-
-__device__ __forceinline__ float block_sum(float v, float *sh)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-    if (lane == 0) sh[wave] = v;
-    __syncthreads();
-    float t = 0.f;
-    for (int w = 0; w < nw; ++w) t += sh[w];
-    __syncthreads();
-    return t;
-}
-
-// grid = M rows.  Row m = b*(k+1)+j.  The j == 0 block of each sequence validates lens[b].
-__global__ __launch_bounds__(256) void embed_kernel(Dims D, StepIO io, const uint16_t *embed, float *X,
-                                                    int32_t *pos_base, int32_t *err_flag)
-{
-    const int m = blockIdx.x, b = m / (io.k + 1), j = m % (io.k + 1);
-    int tok = io.tokens[m];
-    if (tok < 0 || tok >= D.V) {
-        if (threadIdx.x == 0) *err_flag = 1;
-        tok = 0;
-    }
-    if (j == 0 && threadIdx.x == 0) {
-        int len = io.lens[b];
-        if (len < 0 || len + io.k + 1 > D.max_seq) {
-            *err_flag = 1;
-            len = 0;
-        }
-        pos_base[b] = len;
-    }
-    const uint16_t *row = embed + (size_t)tok * D.h;
-    for (int i = threadIdx.x; i < D.h; i += blockDim.x) X[(size_t)m * D.h + i] = bf16_to_f32(row[i]);
-}
-
-// grid = M rows, 256 threads.  a = x * rsqrt(mean(x^2) + eps) * gamma -> packed bf16 hi/lo.
-__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *X, const uint16_t *gamma, int h, int KT,
-                                                           float eps, uint16_t *A_hi, uint16_t *A_lo)
-{
-    __shared__ float sh[4];
-    const int m = blockIdx.x;
-    const float *x = X + (size_t)m * h;
-    float ss = 0.f;
-    for (int i = threadIdx.x; i < h; i += blockDim.x) ss += x[i] * x[i];
-    ss = block_sum(ss, sh);
-    const float r = rsqrtf(ss / (float)h + eps);
-    for (int i = threadIdx.x; i < h; i += blockDim.x) {
-        const float a = x[i] * r * bf16_to_f32(gamma[i]);
-        uint16_t hi, lo;
-        split_bf16(a, hi, lo);
-        const size_t idx = packed_index(m, i, KT);
-        A_hi[idx] = hi;
-        A_lo[idx] = lo;
-    }
-}
-
-// grid = (M, nq + 2*nkv) ; block = d/2 threads.  One (row, head) per block.
-// qkv row layout: [nq*d | nkv*d | nkv*d] fp32.  rope_cs: [max_seq][d/2][2] (cos, sin).
-__global__ void rope_append_kernel(Dims D, const float *qkv, const int32_t *pos_base, int k, const float *rope_cs,
-                                   uint16_t *Qp, uint16_t *Qp_lo, uint16_t *Kc, uint16_t *Vc, int q_rows_pad)
-{
-    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
-    const int b = m / (k + 1), j = m % (k + 1);
-    const int pos = pos_base[b] + j;
-    const int half = D.d >> 1;
-    const float *src = qkv + (size_t)m * (D.qd + 2 * D.kd) + (size_t)head * D.d;
-    const float x0 = src[i], x1 = src[i + half];
-    const size_t slab = ((size_t)b * D.nkv) * D.seq_pad * D.d;  // + kvh * seq_pad * d
-    if (head < D.nq + D.nkv) {
-        const float c = rope_cs[((size_t)pos * half + i) * 2], s = rope_cs[((size_t)pos * half + i) * 2 + 1];
-        const float y0 = x0 * c - x1 * s, y1 = x0 * s + x1 * c;
-        if (head < D.nq) {
-            const int kvh = head / D.g, hl = head % D.g;
-            const int r = j * D.g + hl;
-            const size_t qs = ((size_t)b * D.nkv + kvh) * q_rows_pad * D.d;
-            uint16_t h0, l0, h1, l1;
-            split_bf16(y0, h0, l0);
-            split_bf16(y1, h1, l1);
-            const size_t i0 = qs + packed_index(r, i, D.d >> 5), i1 = qs + packed_index(r, i + half, D.d >> 5);
-            Qp[i0] = h0; Qp_lo[i0] = l0;
-            Qp[i1] = h1; Qp_lo[i1] = l1;
-        } else {
-            const int kvh = head - D.nq;
-            uint16_t *kr = Kc + slab + ((size_t)kvh * D.seq_pad + pos) * D.d;
-            kr[i] = f32_to_bf16(y0);
-            kr[i + half] = f32_to_bf16(y1);
-        }
-    } else {
-        const int kvh = head - D.nq - D.nkv;
-        uint16_t *v = Vc + slab + (size_t)kvh * D.seq_pad * D.d;
-        v[vcache_index(pos, i, D.d)] = f32_to_bf16(x0);
-        v[vcache_index(pos, i + half, D.d)] = f32_to_bf16(x1);
-    }
-}
 
 // grid = M rows, block = 256.  Row arg-max from the LM head's per-tile partials; the lowest
 // token id wins a tie.
@@ -217,31 +123,66 @@ __global__ void lens_kernel(Dims D, int B, int k, const int32_t *lens, int32_t *
     pos_base[b] = len;
 }
 
+// Reorder a row-major bf16 matrix [N][K] into operand tiles (one 16-byte lane record per thread).
+__global__ void pack_weight_kernel(const uint16_t *src, u32x4 *dst, int N, int K, int KT)
+{
+    const size_t rec = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte lane record
+    const size_t total = (size_t)(N >> 4) * KT * 64;
+    if (rec >= total) return;
+    const int lane = (int)(rec & 63);
+    const size_t tile = rec >> 6;
+    const int kt = (int)(tile % KT);
+    const int nt = (int)(tile / KT);
+    const int n = nt * 16 + (lane & 15), k = kt * 32 + 8 * (lane >> 4);
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (k + 8 <= K) {
+        v = *reinterpret_cast<const u32x4 *>(src + (size_t)n * K + k);
+    } else if (k < K) {
+        uint16_t tmp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int e = 0; e < 8 && k + e < K; ++e) tmp[e] = src[(size_t)n * K + k + e];
+        v = *reinterpret_cast<u32x4 *>(tmp);
+    }
+    dst[rec] = v;
+}
+
+
+// grid = M rows, 512 threads.  Validates lens/tokens; x = E[token]; packed x*gamma; sums of squares.
+__global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, const uint16_t *embed, const uint16_t *gamma,
+                                                          float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq,
+                                                          int32_t *pos_base, int32_t *err_flag)
+{
+    const int m = blockIdx.x, b = m / (io.k + 1), j = m % (io.k + 1);
+    int tok = io.tokens[m];
+    if (tok < 0 || tok >= D.V) {
+        if (threadIdx.x == 0) *err_flag = 1;
+        tok = 0;
+    }
+    if (j == 0 && threadIdx.x == 0) {
+        int len = io.lens[b];
+        if (len < 0 || len + io.k + 1 > D.max_seq) {
+            *err_flag = 1;
+            len = 0;
+        }
+        pos_base[b] = len;
+    }
+    const uint16_t *row = embed + (size_t)tok * D.h;
+    const int KT = (D.h + 31) >> 5, NSS = D.h >> 4;
+    for (int i = threadIdx.x; i < D.h; i += blockDim.x) {
+        const float x = bf16_to_f32(row[i]);
+        X[(size_t)m * D.h + i] = x;
+        uint16_t hi, lo;
+        split_bf16(x * bf16_to_f32(gamma[i]), hi, lo);
+        const size_t idx = packed_index(m, i, KT);
+        A_hi[idx] = hi;
+        A_lo[idx] = lo;
+        float ss = x * x;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 16);
+        if ((i & 15) == 0) ssq[(size_t)m * NSS + (i >> 4)] = ss;
+    }
+}
+
 }  // namespace
-
-hipError_t launch_embed(const Dims &D, const StepIO &io, const uint16_t *embed, float *X, int32_t *pos_base,
-                        int32_t *err_flag, hipStream_t s)
-{
-    hipLaunchKernelGGL(embed_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, D, io, embed, X, pos_base, err_flag);
-    return hipGetLastError();
-}
-
-hipError_t launch_rmsnorm_pack(const Dims &D, const float *X, const uint16_t *gamma, int M, uint16_t *A_hi,
-                               uint16_t *A_lo, hipStream_t s)
-{
-    hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(M), dim3(256), 0, s, X, gamma, D.h, (D.h + 31) / 32, D.eps, A_hi, A_lo);
-    return hipGetLastError();
-}
-
-hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *pos_base, int B, int k,
-                              const float *rope_cs, uint16_t *Qp, uint16_t *Qp_lo, uint16_t *Kc_layer, uint16_t *Vc_layer,
-                              hipStream_t s)
-{
-    const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
-    hipLaunchKernelGGL(rope_append_kernel, dim3(B * (k + 1), D.nq + 2 * D.nkv), dim3(D.d / 2), 0, s, D, qkv, pos_base, k,
-                       rope_cs, Qp, Qp_lo, Kc_layer, Vc_layer, q_rows_pad);
-    return hipGetLastError();
-}
 
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
                          int32_t *that, hipStream_t s)
@@ -292,5 +233,24 @@ hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t
                        hipStream_t s)
 {
     hipLaunchKernelGGL(lens_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, pos_base, err_flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weight(const uint16_t *src, uint16_t *dst, int N, int K, hipStream_t s)
+{
+    const int KT = (K + 31) / 32;
+    const size_t total = (size_t)(N / 16) * KT * 64;
+    const int threads = 256;
+    const unsigned blocks = (unsigned)((total + threads - 1) / threads);
+    hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks), dim3(threads), 0, s, src, reinterpret_cast<u32x4 *>(dst), N, K, KT);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
+                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,
+                              hipStream_t s)
+{
+    hipLaunchKernelGGL(fused_embed_kernel, dim3(io.B * (io.k + 1)), dim3(512), 0, s, D, io, embed, gamma, X, A_hi, A_lo, ssq,
+                       pos_base, err_flag);
     return hipGetLastError();
 }

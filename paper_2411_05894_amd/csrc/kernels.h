@@ -2,36 +2,10 @@
 #pragma once
 #include "common.h"
 
-// ---------------------------------------------------------------- GEMM ----
-enum GemmEpilogue {
-    EPI_STORE = 0,   // out_f32[m*ld + n] = acc
-    EPI_RESID = 1,   // out_f32[m*ld + n] += acc                      (O and down projections)
-    EPI_SWIGLU = 2,  // packed bf16 hi/lo of silu(acc(W0)) * acc(W1)  (gate/up projections)
-    EPI_LMHEAD = 3   // per-(row, n-tile) arg-max partial, optional fp32 logits store
-};
-
-struct GemmArgs {
-    const u32x4 *A_hi, *A_lo;  // packed activations [m_tile][k_tile][64 lanes] (lo may be null if !split)
-    const u32x4 *W0, *W1;      // packed weights [n_tile][k_tile][64 lanes]; W1 only for EPI_SWIGLU
-    int KT;                    // k tiles of 32
-    int NT;                    // n tiles of 16 (= grid size)
-    int M;                     // valid rows; rows beyond are computed and dropped
-    float *out_f32;
-    int ld;
-    uint16_t *out_hi, *out_lo; // EPI_SWIGLU destination (packed, KT_out k-tiles)
-    int KT_out;
-    float *logits;             // EPI_LMHEAD: optional [M][ld] store (ld = vocab)
-    float *part_val;           // EPI_LMHEAD: [M][NT]
-    int *part_idx;
-};
-
-// Runs the skinny GEMM for any M (internally in passes of at most 160 rows).
-hipError_t launch_gemm(const GemmArgs &a, int epilogue, bool split, hipStream_t s);
-
+// ---------------------------------------------------------- elementwise ----
 // Reorder a row-major bf16 matrix [N][K] into packed tiles (K padded to 32 with zeros).
 hipError_t launch_pack_weight(const uint16_t *src, uint16_t *dst, int N, int K, hipStream_t s);
 
-// ---------------------------------------------------------- elementwise ----
 struct StepIO {
     const int32_t *tokens, *lens;
     int32_t *accepted_len, *next_token;
@@ -40,17 +14,17 @@ struct StepIO {
 
 // ------------------------------------------------------------ fused GEMMs ----
 enum FusedEpilogue {
-    FEPI_QKV = 0,    // RMSNorm scale, rotary embedding, Q operand packing, KV append; tasks = rotary tile pairs
-    FEPI_RESID = 1,  // X += acc; packed X*gamma_next; sums of squares per 16 columns; tasks = single tiles
-    FEPI_SWIGLU = 2, // RMSNorm scale, silu(gate)*up, operand packing; tasks = (gate tile, up tile)
-    FEPI_LM = 3,     // RMSNorm scale, per-tile arg-max, optional logits; tasks = two consecutive tiles
+    FEPI_QKV = 0,    // RMSNorm scale, rotary embedding, Q operand packing, KV append; units = rotary tile pairs
+    FEPI_RESID = 1,  // X += acc; packed X*gamma_next; sums of squares per 16 columns; units = single tiles
+    FEPI_SWIGLU = 2, // RMSNorm scale, silu(gate)*up, operand packing; units = (gate tile, up tile)
+    FEPI_LM = 3,     // RMSNorm scale, per-tile arg-max, optional logits; units = single tiles
     FEPI_STORE = 4   // out[m][n] = acc (kernel-level entry point only)
 };
 
 struct FusedGemmArgs {
     const u32x4 *A_hi, *A_lo;     // packed activations x*gamma (or attention output / SwiGLU output)
     const u32x4 *W0, *W1, *W2;    // QKV: wq, wk, wv; SWIGLU: gate, up; else W0
-    int KT, NT, n_tasks, M;       // k tiles, n tiles of W0, workgroups, valid rows
+    int KT, NT, M;                // k tiles, n tiles of W0, valid rows
     int h, d, nq, nkv, seq_pad, k, q_rows_pad, vocab;
     float eps;
     const float *ssq_in;          // [M][h/16] sums of squares of the consumed stream (not RESID)
@@ -73,26 +47,19 @@ struct FusedGemmArgs {
     int seg0, seg1;               // tiles of W0 and of W1 in the concatenated output (M > 16 kernel)
     int upw, J, part_rows, kps;   // filled in by the launcher: units per workgroup, K slices, rows per slice, k-tiles per slice
 };
-hipError_t launch_fused_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 // M <= stream_gemm_max_rows(): persistent weight streamer; NT must be the tile count of W0.
 int stream_gemm_max_rows();
 size_t stream_gemm_partial_bytes(const Dims &D, int M);
 size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-level entry point)
-hipError_t launch_stream_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s);
+// Launches the weight-streaming kernel and records its plan (J, part_rows, ...) in `a`; when
+// *needs_epilogue comes back true the results are split-K partials and launch_stream_epilogue
+// must follow with the same `a`.
+hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue);
+hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
                               uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,
                               hipStream_t s);
 
-// Validates lens/tokens (sticky flag, safe substitutes) and gathers embedding rows.
-hipError_t launch_embed(const Dims &D, const StepIO &io, const uint16_t *embed, float *X, int32_t *pos_base,
-                        int32_t *err_flag, hipStream_t s);
-// fp32 rows -> RMS-normalised packed bf16 hi/lo activations (K = h).
-hipError_t launch_rmsnorm_pack(const Dims &D, const float *X, const uint16_t *gamma, int M, uint16_t *A_hi,
-                               uint16_t *A_lo, hipStream_t s);
-// Rotary embedding of Q and K_new, Q to its packed operand buffer, K/V rows into the cache.
-hipError_t launch_rope_append(const Dims &D, const float *qkv, const int32_t *pos_base, int B, int k,
-                              const float *rope_cs, uint16_t *Qp, uint16_t *Qp_lo, uint16_t *Kc_layer, uint16_t *Vc_layer,
-                              hipStream_t s);
 // Merge per-tile arg-max partials, then greedy prefix acceptance.
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
                          int32_t *that_dbg, hipStream_t s);
@@ -120,37 +87,3 @@ struct AttnArgs {
     int B, k;
 };
 hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s);
-
-// ------------------------------------------------- persistent step kernel ----
-struct LayerPtrs {
-    const uint16_t *wq, *wk, *wv, *wo, *wg, *wu, *wd;  // packed
-    const uint16_t *attn_norm, *mlp_norm;
-};
-
-enum { AK_QKV = 0, AK_ATT = 1, AK_GU = 2, AK_F = 3 };  // input of QKV / LM head, attention output, input of gate/up, SwiGLU output
-
-struct MegaArgs {
-    Dims D;
-    StepIO io;
-    const LayerPtrs *layers;  // device array [L]
-    const uint16_t *embed, *lm_head, *final_norm;
-    float *X, *ssq;           // residual stream [M][h]; sums of squares per 16 columns, [2L+1 versions][48][h/16]
-    uint16_t *A[4];           // packed bf16 operand buffers by role (AK_*), [versions][hi half | lo half]
-    size_t A_stride[4];       // bf16 elements per version
-    size_t A_half[4];         // bf16 elements of the hi half (the lo half follows)
-    uint16_t *Qp, *Qp_lo, *Kc, *Vc;
-    float *part_o, *part_ml, *part_val;
-    int *part_idx;
-    int32_t *pos_base, *err_flag, *that_dbg;
-    const float *rope_cs;
-    unsigned *bar;            // [0] barrier arrivals, [1] give-up flag
-    float *dbg_logits, *dbg_hidden;
-    unsigned long long *tstamps;  // optional: constant-rate clock of workgroup 0 at the start of every phase, and at the end
-    size_t kv_layer_elems;
-    int q_rows_pad;
-    int phase_lo, phase_hi;   // phases to run; more than one needs a cooperative launch
-};
-
-int mega_max_rows();
-hipError_t mega_occupancy(int M, int *blocks_per_cu);
-hipError_t launch_mega(const MegaArgs &a, int grid, bool cooperative, hipStream_t s);

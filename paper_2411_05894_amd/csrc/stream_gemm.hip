@@ -16,7 +16,7 @@
 //                  waves owns 256 output columns and one k-slice; each wave streams the weights of
 //                  its own 64 columns HBM -> registers (rolling prefetch, every weight byte read
 //                  once), while the activation k-tiles, which all four waves need, are staged
-//                  through a three-deep LDS ring.  The 16-row operand tiles of the packed layout
+//                  through a register ring and a two-deep LDS ring.  The 16-row operand tiles of the packed layout
 //                  are read as the halves of 32-row MFMA operands, so one weight layout serves
 //                  both kernels.  Results go to split-K partials for epi_kernel.
 //   epi_kernel     Sums split-K partial results (when K is split over workgroups) in fixed order
@@ -292,6 +292,17 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int units_per
 }
 
 
+template <int EPI> hipError_t launch_epi(const FusedGemmArgs &a, hipStream_t s)
+{
+    const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
+    const int row_tiles = (a.M + 15) / 16;
+    const int blocks_x = (4 * n_cu + row_tiles - 1) / row_tiles;
+    int upb = (a.n_units + blocks_x - 1) / blocks_x;
+    if (upb < 1) upb = 1;
+    hipLaunchKernelGGL((epi_kernel<EPI>), dim3((a.n_units + upb - 1) / upb, row_tiles), dim3(256), 0, s, a, upb);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------- M > 16 ----
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
@@ -335,7 +346,7 @@ __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_b
     constexpr int MT16 = 2 * MT32;
     constexpr int CHUNK = MT16 * 2 * 64;          // lane records of one activation k-tile (hi and lo)
     constexpr int APT = CHUNK / (QW * 64);        // records staged per thread
-    __shared__ u32x4 ring[3][CHUNK];
+    __shared__ u32x4 ring[2][CHUNK];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int J = a.J, j = blockIdx.x % J, grp = blockIdx.x / J;
     const int KT = a.KT;
@@ -382,24 +393,23 @@ __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_b
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.f;
 
-    // prologue: weights of the first QDW k-tiles, activation chunks 0 and 1
-    u32x4 w[QDW][QNG][2];
-#pragma unroll
-    for (int u = 0; u < QDW; ++u) {
-        const int kt = kt_begin + (u < n_iter ? u : n_iter - 1);
+    // All loads of a wave retire in issue order, so the activation loads (L2 hits) are issued
+    // QDW k-tiles ahead, each right before the weight loads of the same k-tile, and parked in
+    // registers: by the time chunk c moves to LDS (iteration c-1) everything issued before it has
+    // been consumed already, and waiting for it never waits for a weight load still in flight.
+    u32x4 w[QDW][QNG][2], apre[QDW][APT];
+    auto issue = [&](int u, int it) {   // activation chunk and weights of iteration `it` into slot u
+        const int kt = kt_begin + (it < n_iter ? it : n_iter - 1);
+        stage_load(kt, apre[u]);
 #pragma unroll
         for (int g = 0; g < QNG; ++g) {
             w[u][g][0] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r0);
             w[u][g][1] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r1);
         }
-    }
-    {
-        u32x4 v[APT];
-        stage_load(kt_begin, v);
-        stage_store(0, v);
-        stage_load(kt_begin + (n_iter > 1 ? 1 : 0), v);
-        stage_store(1, v);
-    }
+    };
+#pragma unroll
+    for (int u = 0; u < QDW; ++u) issue(u, u);
+    stage_store(0, apre[0]);
     __syncthreads();
 
     for (int it0 = 0; it0 < n_iter; it0 += QDW) {
@@ -407,10 +417,7 @@ __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_b
         for (int u = 0; u < QDW; ++u) {
             const int it = it0 + u;
             if (it < n_iter) {
-                u32x4 apre[APT];
-                const bool more_a = it + 2 < n_iter;
-                if (more_a) stage_load(kt_begin + it + 2, apre);
-                const u32x4 *buf = ring[it % 3];
+                const u32x4 *buf = ring[it & 1];
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh) {
                     const int rec = hh ? r1 : r0;
@@ -426,17 +433,10 @@ __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_b
                         }
                     }
                 }
-                if (it + QDW < n_iter) {
-                    const int kt = kt_begin + it + QDW;
-#pragma unroll
-                    for (int g = 0; g < QNG; ++g) {
-                        w[u][g][0] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r0);
-                        w[u][g][1] = __builtin_nontemporal_load(wp[g] + (size_t)kt * 64 + r1);
-                    }
-                }
-                // Ring slot (it+2)%3 held chunk it-1, which every wave finished before the barrier
+                if (it + QDW < n_iter) issue(u, it + QDW);
+                // LDS slot (it+1)&1 held chunk it-1, which every wave finished before the barrier
                 // that ended iteration it-1.
-                if (more_a) stage_store((it + 2) % 3, apre);
+                if (it + 1 < n_iter) stage_store((it + 1) & 1, apre[(u + 1) % QDW]);
                 __syncthreads();
             }
         }
@@ -476,8 +476,9 @@ __host__ QPlan q_plan(int Ntot, int K)
     return p;
 }
 
-template <int EPI> hipError_t launch_large(FusedGemmArgs a, hipStream_t s)
+template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue)
 {
+    *needs_epilogue = true;
     const int NT16 = a.Ntot / 16;
     const QPlan p = q_plan(a.Ntot, a.KT * 32);
     a.J = p.J;
@@ -500,16 +501,10 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs a, hipStream_t s)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
-    const int row_tiles = (a.M + 15) / 16;
-    int blocks_x = (4 * n_cu + row_tiles - 1) / row_tiles;
-    int upb = (a.n_units + blocks_x - 1) / blocks_x;
-    if (upb < 1) upb = 1;
-    hipLaunchKernelGGL((epi_kernel<EPI>), dim3((a.n_units + upb - 1) / upb, row_tiles), dim3(256), 0, s, a, upb);
-    return hipGetLastError();
+    return hipSuccess;
 }
 
-template <int EPI> hipError_t launch_small(FusedGemmArgs a, hipStream_t s)
+template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue)
 {
     // k-tiles per wave: 7 when K is a multiple of 16*7*32 but not of 16*8*32 (the FFN widths of the
     // Llama shapes), else 8; a ragged K split is legal either way.
@@ -525,11 +520,7 @@ template <int EPI> hipError_t launch_small(FusedGemmArgs a, hipStream_t s)
     if (a.J > 1 && (size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
     if (seven) hipLaunchKernelGGL((pgemm_kernel<EPI, 7>), dim3(groups * a.J), dim3(PW * 64), 0, s, a);
     else hipLaunchKernelGGL((pgemm_kernel<EPI, 8>), dim3(groups * a.J), dim3(PW * 64), 0, s, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.J == 1) return e;
-    int upb = (a.n_units + 4 * n_cu - 1) / (4 * n_cu);
-    if (upb < 1) upb = 1;
-    hipLaunchKernelGGL((epi_kernel<EPI>), dim3((a.n_units + upb - 1) / upb, 1), dim3(256), 0, s, a, upb);
+    *needs_epilogue = a.J > 1;
     return hipGetLastError();
 }
 
@@ -581,22 +572,33 @@ size_t stream_gemm_scratch_bytes(int M, int N, int K)
     return j > 1 ? j * 16 * N * sizeof(float) : 0;
 }
 
-hipError_t launch_stream_gemm(const FusedGemmArgs &a, int epilogue, hipStream_t s)
+hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue)
 {
     if (a.M > stream_gemm_max_rows()) {
         switch (epilogue) {
-        case FEPI_QKV: return launch_large<FEPI_QKV>(a, s);
-        case FEPI_RESID: return launch_large<FEPI_RESID>(a, s);
-        case FEPI_SWIGLU: return launch_large<FEPI_SWIGLU>(a, s);
-        case FEPI_STORE: return launch_large<FEPI_STORE>(a, s);
-        default: return launch_large<FEPI_LM>(a, s);
+        case FEPI_QKV: return launch_large<FEPI_QKV>(a, s, needs_epilogue);
+        case FEPI_RESID: return launch_large<FEPI_RESID>(a, s, needs_epilogue);
+        case FEPI_SWIGLU: return launch_large<FEPI_SWIGLU>(a, s, needs_epilogue);
+        case FEPI_STORE: return launch_large<FEPI_STORE>(a, s, needs_epilogue);
+        default: return launch_large<FEPI_LM>(a, s, needs_epilogue);
         }
     }
     switch (epilogue) {
-    case FEPI_QKV: return launch_small<FEPI_QKV>(a, s);
-    case FEPI_RESID: return launch_small<FEPI_RESID>(a, s);
-    case FEPI_SWIGLU: return launch_small<FEPI_SWIGLU>(a, s);
-    case FEPI_STORE: return launch_small<FEPI_STORE>(a, s);
-    default: return launch_small<FEPI_LM>(a, s);
+    case FEPI_QKV: return launch_small<FEPI_QKV>(a, s, needs_epilogue);
+    case FEPI_RESID: return launch_small<FEPI_RESID>(a, s, needs_epilogue);
+    case FEPI_SWIGLU: return launch_small<FEPI_SWIGLU>(a, s, needs_epilogue);
+    case FEPI_STORE: return launch_small<FEPI_STORE>(a, s, needs_epilogue);
+    default: return launch_small<FEPI_LM>(a, s, needs_epilogue);
+    }
+}
+
+hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s)
+{
+    switch (epilogue) {
+    case FEPI_QKV: return launch_epi<FEPI_QKV>(a, s);
+    case FEPI_RESID: return launch_epi<FEPI_RESID>(a, s);
+    case FEPI_SWIGLU: return launch_epi<FEPI_SWIGLU>(a, s);
+    case FEPI_STORE: return launch_epi<FEPI_STORE>(a, s);
+    default: return launch_epi<FEPI_LM>(a, s);
     }
 }

@@ -3,7 +3,7 @@
 // profiler runs that need a plain executable (hardware-counter collection), and it includes
 // a plain copy kernel of known traffic (--copy-gib) to calibrate byte counters against.
 //
-//   step_driver --shape 8b --batch 1 --ctx 2048 --k 8 --steps 5 [--mode 0..3] [--copy-gib 1]
+//   step_driver --shape 8b --batch 1 --ctx 2048 --k 8 --steps 5 [--copy-gib 1]
 #include "../../include/sssd_verify.h"
 
 #include <hip/hip_runtime.h>
@@ -65,7 +65,7 @@ __global__ void calibration_copy_kernel(const uint4 *src, uint4 *dst, size_t n)
 int main(int argc, char **argv)
 {
     std::string shape = "8b";
-    int B = 1, ctx = 2048, k = 8, steps = 5, warmup = 2, mode = 0;
+    int B = 1, ctx = 2048, k = 8, steps = 5, warmup = 2;
     double copy_gib = 0.0;
     for (int i = 1; i + 1 < argc; i += 2) {
         const std::string f = argv[i];
@@ -76,7 +76,6 @@ int main(int argc, char **argv)
         else if (f == "--k") k = std::atoi(v);
         else if (f == "--steps") steps = std::atoi(v);
         else if (f == "--warmup") warmup = std::atoi(v);
-        else if (f == "--mode") mode = std::atoi(v);
         else if (f == "--copy-gib") copy_gib = std::atof(v);
         else { std::fprintf(stderr, "unknown flag %s\n", f.c_str()); return 2; }
     }
@@ -128,7 +127,6 @@ int main(int argc, char **argv)
     if (!in_place) CK(hipMalloc(&pk, pk_b));
     sssd_ctx *vc = nullptr;
     SK(sssd_verify_init(&cfg, &w, kv, kv_b, ws, ws_b, pk, in_place ? 0 : pk_b, in_place ? SSSD_PACK_IN_PLACE : 0, &vc));
-    SK(sssd_verify_set_mode(vc, mode));
     // cache contents: finite pseudo-random rows everywhere (import is not needed for timing)
     hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, 0, (uint16_t *)kv, kv_b / 2, 12345u, 2.4f);
     int32_t *tok, *lens, *acc, *nxt;
@@ -147,8 +145,8 @@ int main(int argc, char **argv)
     float ms = 0.f;
     CK(hipEventElapsedTime(&ms, e0, e1));
     SK(sssd_verify_sync(vc, nullptr));
-    std::printf("{\"shape\": \"%s\", \"B\": %d, \"ctx\": %d, \"k\": %d, \"mode\": %d, \"steps\": %d, \"ms_per_step\": %.4f}\n",
-                shape.c_str(), B, ctx, k, mode, steps, ms / steps);
+    std::printf("{\"shape\": \"%s\", \"B\": %d, \"ctx\": %d, \"k\": %d, \"steps\": %d, \"ms_per_step\": %.4f}\n",
+                shape.c_str(), B, ctx, k, steps, ms / steps);
     SK(sssd_verify_destroy(vc));
     return 0;
 }

@@ -31,7 +31,7 @@ class Pair:
     """A library context and an oracle model over identical weights."""
 
     def __init__(self, shape, seed: int, max_batch: int, max_k: int, max_seq: int, unit_gains: bool = True,
-                 in_place: bool = False, oracle_batch: Optional[int] = None, mode: int = sv.SSSD_MODE_AUTO):
+                 in_place: bool = False, oracle_batch: Optional[int] = None):
         dev = torch.device("cuda:0")
         self.shape = shape
         layers, g = gen_weights(shape, seed, dev, unit_gains)
@@ -39,7 +39,6 @@ class Pair:
         self.oracle = oracle.OracleModel(shape, hl, hg, oracle_batch or max_batch, max_seq)
         self.cfg = sv.make_config(shape, max_batch, max_k, max_seq)
         self.ctx = sv.VerifyContext(self.cfg, layers, g, in_place=in_place)
-        self.ctx.sssd_verify_set_mode(mode)
         if not in_place:
             del layers          # the packed copy is what the kernels read
         self.dev = dev

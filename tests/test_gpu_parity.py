@@ -103,17 +103,12 @@ def test_attention_vs_oracle(shape_name, B, k, ctxs):
 
 
 # ----------------------------------------------------- cfg 1: tiny chain ----
-MODES = [pytest.param(sv.SSSD_MODE_AUTO, id="fused"), pytest.param(sv.SSSD_MODE_KERNELS, id="kernels"), pytest.param(sv.SSSD_MODE_PHASES, id="phases"),
-         pytest.param(sv.SSSD_MODE_PERSISTENT, id="persistent")]
-
-
-@pytest.mark.parametrize("mode", MODES)
-def test_tiny_chained_verify_steps(mode):
+def test_tiny_chained_verify_steps():
     """Tiny model, B=1, 128-token prompt, k=4 drafts from the oracle's greedy continuation with
     one token replaced at a seeded position in 0..4 (4 = no replacement), 64 chained steps."""
     s = MODEL_SHAPES["tiny"]
     k, prompt_len, steps = 4, 128, 64
-    p = Pair(s, seed=1, max_batch=1, max_k=k, max_seq=prompt_len + steps * (k + 1) + 8, mode=mode)
+    p = Pair(s, seed=1, max_batch=1, max_k=k, max_seq=prompt_len + steps * (k + 1) + 8)
     prompt = uniform_int(2, 5, (prompt_len,), 0, s.vocab - 1)
     # prefill rows 0..126 through the verify step itself, in chunks of k+1, on both sides
     lens = 0
@@ -149,11 +144,10 @@ def test_tiny_chained_verify_steps(mode):
     assert exempt < rows // 2
 
 
-@pytest.mark.parametrize("mode", MODES)
-def test_tiny_batched_ragged_and_rollback(mode):
+def test_tiny_batched_ragged_and_rollback():
     s = MODEL_SHAPES["tiny"]
     B, k = 5, 7
-    p = Pair(s, seed=3, max_batch=B, max_k=k, max_seq=200, unit_gains=False, mode=mode)
+    p = Pair(s, seed=3, max_batch=B, max_k=k, max_seq=200, unit_gains=False)
     ctxs = [0, 1, 31, 64, 150]
     for b in range(B):
         p.prefill_random_kv(11, b, ctxs[b], oracle_slot=b)
@@ -179,10 +173,9 @@ def test_tiny_batched_ragged_and_rollback(mode):
     compare_step(gpu2, ref2, tok2)
 
 
-@pytest.mark.parametrize("mode", MODES)
-def test_error_reporting(mode):
+def test_error_reporting():
     s = MODEL_SHAPES["tiny"]
-    p = Pair(s, seed=1, max_batch=2, max_k=4, max_seq=64, mode=mode)
+    p = Pair(s, seed=1, max_batch=2, max_k=4, max_seq=64)
     t = torch.zeros(2, 5, dtype=torch.int32, device=DEV)
     out = torch.zeros(2, dtype=torch.int32, device=DEV)
     lens = torch.tensor([10, 60], dtype=torch.int32, device=DEV)            # 60 + 5 > 64
@@ -200,10 +193,9 @@ def test_error_reporting(mode):
     assert ei.value.code == sv.SSSD_ECAPACITY
 
 
-@pytest.mark.parametrize("mode", MODES)
-def test_step_is_deterministic(mode):
+def test_step_is_deterministic():
     s = MODEL_SHAPES["tiny"]
-    p = Pair(s, seed=1, max_batch=2, max_k=4, max_seq=64, mode=mode)
+    p = Pair(s, seed=1, max_batch=2, max_k=4, max_seq=64)
     tokens = uniform_int(13, 1, (2, 5), 0, s.vocab - 1)
     a = p.step(tokens, torch.tensor([0, 0]))["logits"].clone()
     b = p.step(tokens, torch.tensor([0, 0]))["logits"]
