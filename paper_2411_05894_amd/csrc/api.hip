@@ -89,13 +89,6 @@ Dims make_dims(const sssd_model_config *c)
     D.max_batch = c->max_batch; D.max_k = c->max_k; D.max_seq = c->max_seq;
     D.seq_pad = round_up(c->max_seq, 32);
     D.eps = c->rms_eps; D.rope_base = c->rope_base;
-    // Attention split: aim at ~2048 waves over (sequence, kv head, chunk) at full capacity.
-    long chunk = ((long)D.seq_pad * D.max_batch * D.nkv + 2047) / 2048;
-    chunk = (chunk + 31) / 32 * 32;
-    if (chunk < 64) chunk = 64;
-    if (chunk > 2048) chunk = 2048;
-    D.chunk = (int)chunk;
-    D.max_splits = (D.seq_pad + D.chunk - 1) / D.chunk;
     return D;
 }
 
@@ -124,7 +117,12 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.Af_lo = (uint16_t *)take(S.tiles_alloc * KTf * 1024);
     b.Qp = (uint16_t *)take((size_t)D.max_batch * D.nkv * S.q_rows_pad * D.d * 2);
     b.Qp_lo = (uint16_t *)take((size_t)D.max_batch * D.nkv * S.q_rows_pad * D.d * 2);
-    const size_t prow = (size_t)D.max_batch * D.nkv * D.max_splits * S.q_rows_pad;
+    size_t slots = 0;   // attention partial slots: the most any batch size needs
+    for (int B = 1; B <= D.max_batch; ++B) {
+        const size_t need = (size_t)B * D.nkv * attention_splits(D, B);
+        if (need > slots) slots = need;
+    }
+    const size_t prow = slots * S.q_rows_pad;
     b.part_o = (float *)take(prow * D.d * 4);
     b.part_ml = (float *)take(prow * 2 * 4);
     b.part_val = (float *)take((size_t)S.m_alloc * NTv * 4);
@@ -422,7 +420,7 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         f.n_units = (D.nq + 2 * D.nkv) * (D.d / 32); f.Ntot = D.qd + 2 * D.kd;
         HIP_TRY(fgemm(FEPI_QKV));
         {
-            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
+            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
             Prof p(c, s, SSSD_PROF_ATTN);
             HIP_TRY(launch_attention(D, a, s));
         }
@@ -595,7 +593,7 @@ int sssd_op_attention(sssd_ctx *c, int32_t layer, int32_t B, int32_t k, const fl
     HIP_TRY(launch_lens(D, B, k, lens, W.pos_base, W.err_flag, s));
     HIP_TRY(launch_q_pack(D, q, B, k, W.Qp, W.Qp_lo, s));
     uint16_t *Kl = c->Kc + (size_t)layer * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)layer * c->S.kv_layer_elems;
-    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k};
+    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
     HIP_TRY(launch_attention(D, a, s));
     HIP_TRY(launch_unpack_act(W.Aq_hi, W.Aq_lo, B * (k + 1), D.qd, out, s));
     return SSSD_OK;

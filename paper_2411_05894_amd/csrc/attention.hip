@@ -6,10 +6,14 @@
 // is "row j sees positions 0 .. lens[b]+j" and is applied arithmetically (no mask
 // tensor is read).
 //
-// One wavefront owns one (sequence, kv head, position chunk): all g*(k+1) query
-// rows that share the kv head ride in the MFMA column dimension, so every cached
-// byte is read once per step.  Per block of 32 positions:
-//   S^T = K . Q^T        (A operand = 16 cached K rows straight from memory)
+// One workgroup owns one (sequence, kv head, position chunk).  All g*(k+1) query rows
+// that share the kv head are processed against the chunk, one 16-row tile per wave,
+// so every cached byte is read from HBM once per step: the waves stage each block of
+// 32 positions through LDS together (double buffered, the next block's loads in flight
+// during the current block's arithmetic) and every wave reads its operands from there.
+// Per block and wave:
+//   S^T = K . Q^T        (A operand = 16 cached K rows; LDS rows are padded by 16 bytes so
+//                         the 16 rows a quarter-wave reads fall into distinct banks)
 //   online softmax in registers; the row statistics need only two cross-lane xors
 //   O^T += V^T . P^T     (A operand = V in its block-transposed cache order,
 //                         B operand = the lane's own probabilities)
@@ -26,209 +30,255 @@ __device__ __forceinline__ f32x4 mfma(const u32x4 &a, const u32x4 &b, f32x4 c)
 }
 
 constexpr float NEG_BIG = -1.0e30f;
+constexpr int MAX_WAVES = 6;   // query-row tiles per launch
 
-template <int HD, int RT>
-__global__ __launch_bounds__(64) void attn_partial_kernel(Dims D, AttnArgs a, int q_rows_pad, int rt_base)
+// grid = (splits, kv heads, sequences); block = NW waves; wave w owns query-row tile rt_base + w.
+template <int HD, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_partial_kernel(Dims D, AttnArgs a, int q_rows_pad, int rt_base)
 {
     constexpr int KS = HD / 32, DT = HD / 16;
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+    constexpr int CPR = HD / 8;          // 16-byte records per cached K row
+    constexpr int KROW = CPR + 1;        // LDS row pitch in records (one record of padding)
+    constexpr int NREC = 32 * CPR;       // records of a 32-position block, K and V alike
+    constexpr int T = NW * 64;
+    constexpr int SPT = (NREC + T - 1) / T;   // records staged per thread and operand
+    __shared__ u32x4 Ks[2][32 * KROW];
+    __shared__ u32x4 Vs[2][NREC];
+
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int q = lane >> 4, c = lane & 15;
     const int len = a.pos_base[b];
     const int total = len + a.k + 1;
-    const int t_begin = split * D.chunk;
+    const int t_begin = split * a.chunk;
     if (t_begin >= total) return;
-    const int t_end = min(total, t_begin + D.chunk);
+    const int t_end = min(total, t_begin + a.chunk);
 
     const size_t slab = ((size_t)b * D.nkv + kvh) * D.seq_pad * HD;
-    const uint16_t *Kc = a.Kc + slab;
+    const u32x4 *Kc = reinterpret_cast<const u32x4 *>(a.Kc + slab);
     const u32x4 *Vc = reinterpret_cast<const u32x4 *>(a.Vc + slab);
-    const u32x4 *Qs = reinterpret_cast<const u32x4 *>(a.Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD);
-    const u32x4 *Ql = reinterpret_cast<const u32x4 *>(a.Qp_lo + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD);
+    const int rt = rt_base + wave;
+    const u32x4 *Qs = reinterpret_cast<const u32x4 *>(a.Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD) + (size_t)rt * KS * 64 + lane;
+    const u32x4 *Ql = reinterpret_cast<const u32x4 *>(a.Qp_lo + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD) + (size_t)rt * KS * 64 + lane;
+
+    // staging: record i of a block; K rows are contiguous in the cache, so is a whole V block
+    u32x4 kst[SPT], vst[SPT];
+    auto stage_load = [&](int t0) {
+#pragma unroll
+        for (int i = 0; i < SPT; ++i) {
+            const int rec = threadIdx.x + i * T;
+            if (NREC % T == 0 || rec < NREC) {
+                kst[i] = Kc[(size_t)t0 * CPR + rec];
+                vst[i] = Vc[(size_t)(t0 >> 5) * NREC + rec];
+            }
+        }
+    };
+    auto stage_store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < SPT; ++i) {
+            const int rec = threadIdx.x + i * T;
+            if (NREC % T == 0 || rec < NREC) {
+                Ks[buf][(rec / CPR) * KROW + rec % CPR] = kst[i];
+                Vs[buf][rec] = vst[i];
+            }
+        }
+    };
+    stage_load(t_begin);
 
     // q ~= hi + lo (two bf16), so the scores carry fp32-level accuracy although K is bf16.
-    u32x4 qreg[RT][KS], qlo[RT][KS];
+    u32x4 qreg[KS], qlo[KS];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qreg[rt][ks] = Qs[((size_t)(rt_base + rt) * KS + ks) * 64 + lane];
-            qlo[rt][ks] = Ql[((size_t)(rt_base + rt) * KS + ks) * 64 + lane];
-        }
-
-    f32x4 o[RT][DT];
-    float m_run[RT], l_run[RT];
-    int limit[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        m_run[rt] = NEG_BIG;
-        l_run[rt] = 0.f;
-        int j = ((rt_base + rt) * 16 + c) / D.g;   // query row -> draft index
-        if (j > a.k) j = a.k;
-        limit[rt] = len + j;                        // last visible position
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < KS; ++ks) {
+        qreg[ks] = Qs[ks * 64];
+        qlo[ks] = Ql[ks * 64];
     }
+    f32x4 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = NEG_BIG, l_run = 0.f;
+    int j = (rt * 16 + c) / D.g;   // query row -> draft index
+    if (j > a.k) j = a.k;
+    const int limit = len + j;     // last visible position
     const float scale = 1.4426950408889634f * rsqrtf((float)HD);  // log2(e)/sqrt(d)
 
-    for (int t0 = t_begin; t0 < t_end; t0 += 32) {
-        u32x4 kreg[2][KS];
+    stage_store(0);
+    __syncthreads();
+
+    int buf = 0;
+    for (int t0 = t_begin; t0 < t_end; t0 += 32, buf ^= 1) {
+        const bool more = t0 + 32 < t_end;
+        if (more) stage_load(t0 + 32);
+
+        f32x4 s[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            s[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 kk = Ks[buf][(16 * u + c) * KROW + ks * 4 + q];
+                s[u] = mfma(kk, qreg[ks], s[u]);
+                s[u] = mfma(kk, qlo[ks], s[u]);
+            }
+        }
+        // s[u][r] is the score of position t0 + 16u + 4q + r for query row rt*16 + c.
+        float v[8];
+        float mx = NEG_BIG;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kreg[u][ks] = *reinterpret_cast<const u32x4 *>(Kc + (size_t)(t0 + 16 * u + c) * HD + ks * 32 + 8 * q);
-        u32x4 vreg[DT];
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vreg[dt] = Vc[((size_t)(t0 >> 5) * DT + dt) * 64 + lane];
-
-        u32x4 pb[RT], pl[RT];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            f32x4 s[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                s[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s[u] = mfma(kreg[u][ks], qreg[rt][ks], s[u]);
-                    s[u] = mfma(kreg[u][ks], qlo[rt][ks], s[u]);
-                }
+            for (int r = 0; r < 4; ++r) {
+                const int t = t0 + 16 * u + 4 * q + r;
+                float x = s[u][r] * scale;
+                if (t > limit) x = NEG_BIG;
+                v[u * 4 + r] = x;
+                mx = fmaxf(mx, x);
             }
-            // s[u][r] is the score of position t0 + 16u + 4q + r for query row rt*16 + c.
-            float v[8];
-            float mx = NEG_BIG;
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+        uint32_t pk[4], pkl[4];
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int t = t0 + 16 * u + 4 * q + r;
-                    float x = s[u][r] * scale;
-                    if (t > limit[rt]) x = NEG_BIG;
-                    v[u * 4 + r] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[rt], mx);
-            const float alpha = exp2f(m_run[rt] - m_new);
-            m_run[rt] = m_new;
-            float psum = 0.f;
-            uint32_t pk[4], pkl[4];
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const float p0 = exp2f(v[e] - m_new), p1 = exp2f(v[e + 1] - m_new);
-                uint16_t h0, l0, h1, l1;   // p ~= hi + lo: the probabilities keep ~16 mantissa bits
-                split_bf16(p0, h0, l0);
-                split_bf16(p1, h1, l1);
-                psum += p0 + p1;
-                pk[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                pkl[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-            }
-            l_run[rt] = l_run[rt] * alpha + psum;
-            pb[rt] = u32x4{pk[0], pk[1], pk[2], pk[3]};
-            pl[rt] = u32x4{pkl[0], pkl[1], pkl[2], pkl[3]};
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                o[rt][dt] *= alpha;
-            }
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = exp2f(v[e] - m_new), p1 = exp2f(v[e + 1] - m_new);
+            uint16_t h0, l0, h1, l1;   // p ~= hi + lo: the probabilities keep ~16 mantissa bits
+            split_bf16(p0, h0, l0);
+            split_bf16(p1, h1, l1);
+            psum += p0 + p1;
+            pk[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            pkl[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
+        l_run = l_run * alpha + psum;
+        const u32x4 pb = u32x4{pk[0], pk[1], pk[2], pk[3]}, pl = u32x4{pkl[0], pkl[1], pkl[2], pkl[3]};
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                o[rt][dt] = mfma(vreg[dt], pb[rt], o[rt][dt]);
-                o[rt][dt] = mfma(vreg[dt], pl[rt], o[rt][dt]);
-            }
+        for (int dt = 0; dt < DT; ++dt) {
+            const u32x4 vv = Vs[buf][dt * 64 + lane];
+            o[dt] *= alpha;
+            o[dt] = mfma(vv, pb, o[dt]);
+            o[dt] = mfma(vv, pl, o[dt]);
+        }
+
+        // Buffer buf^1 was read in the previous iteration, which every wave left through the
+        // barrier below before anyone got here.
+        if (more) stage_store(buf ^ 1);
+        __syncthreads();
     }
 
-    // o[rt][dt][r] of lane (q, c): channel dt*16 + 4q + r of query row rt*16 + c.
-    const size_t slot = ((size_t)b * D.nkv + kvh) * D.max_splits + split;
+    // o[dt][r] of lane (q, c): channel dt*16 + 4q + r of query row rt*16 + c.
+    const size_t slot = ((size_t)b * D.nkv + kvh) * a.n_splits + split;
+    float l = l_run;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const size_t row = slot * q_rows_pad + (size_t)rt * 16 + c;
+    float *po = a.part_o + row * HD;
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        float l = l_run[rt];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        const size_t row = slot * q_rows_pad + (size_t)(rt_base + rt) * 16 + c;
-        float *po = a.part_o + row * HD;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(po + dt * 16 + 4 * q) = o[rt][dt];
-        if (q == 0) {
-            a.part_ml[row * 2] = m_run[rt];
-            a.part_ml[row * 2 + 1] = l;
-        }
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(po + dt * 16 + 4 * q) = o[dt];
+    if (q == 0) {
+        a.part_ml[row * 2] = m_run;
+        a.part_ml[row * 2 + 1] = l;
     }
 }
 
-// One wave per (sequence, kv head, query row); 4 waves per block.  Lanes first work across
-// chunks (weights), then across channels (values, eight chunks' loads in flight at a time).
+// One wave per (sequence, kv head, query row); 4 waves per block.  The wave reads the row's
+// partial outputs of up to 4*BATCH chunks in one round of independent loads: lanes 16s..16s+15
+// take chunk s, s+4, ... with 8 channels each, and the four lane groups are summed at the end
+// in fixed order.
+template <int HD>
 __global__ __launch_bounds__(256) void attn_combine_kernel(Dims D, AttnArgs a, int q_rows_pad)
 {
+    constexpr int BATCH = 9;
+    constexpr int LPR = HD / 8;   // lanes that cover a row of HD channels, 8 each
     const int lane = threadIdx.x & 63, k = a.k;
     const int R = D.g * (k + 1);
     const int n_tasks = a.B * D.nkv * R;
     const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (task >= n_tasks) return;
     const int KTq = (D.qd + 31) >> 5;
-    const int ch = lane * 2;  // head_dim 128: two channels per lane; head_dim 64: lanes 0..31
+    const int sg = lane >> 4, cl = lane & 15;
     const int r = task % R, kvh = (task / R) % D.nkv, b = task / (R * D.nkv);
     const int total = a.pos_base[b] + k + 1;
-    const int n_splits = (total + D.chunk - 1) / D.chunk;
-    const size_t slot0 = ((size_t)b * D.nkv + kvh) * D.max_splits;
-    float m_star = NEG_BIG;
-    for (int s = lane; s < n_splits; s += 64) m_star = fmaxf(m_star, a.part_ml[((slot0 + s) * q_rows_pad + r) * 2]);
+    const int n_splits = (total + a.chunk - 1) / a.chunk;   // at most 64 (launch_attention)
+    const size_t slot0 = ((size_t)b * D.nkv + kvh) * a.n_splits;
+
+    float2 ml = float2{NEG_BIG, 0.f};
+    if (lane < n_splits) ml = *reinterpret_cast<const float2 *>(a.part_ml + ((slot0 + lane) * q_rows_pad + r) * 2);
+    float num[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float m_star = 0.f, w_lane = 0.f;
+    for (int base = 0; base < n_splits; base += 4 * BATCH) {
+        f32x4 pv[BATCH][2];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) m_star = fmaxf(m_star, __shfl_xor(m_star, off));
-    float den = 0.f, num0 = 0.f, num1 = 0.f;
-    for (int base = 0; base < n_splits; base += 64) {
-        const int s_mine = base + lane;
-        float w_lane = 0.f;
-        if (s_mine < n_splits) {
-            const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((slot0 + s_mine) * q_rows_pad + r) * 2);
-            w_lane = exp2f(ml.x - m_star);
-            den += w_lane * ml.y;
+        for (int u = 0; u < BATCH; ++u) {
+            const int s = base + 4 * u + sg;
+            const bool live = s < n_splits && cl < LPR;
+            const f32x4 *p = reinterpret_cast<const f32x4 *>(a.part_o + ((slot0 + (live ? s : 0)) * q_rows_pad + r) * HD + (cl < LPR ? cl : 0) * 8);
+            pv[u][0] = live ? p[0] : f32x4{0.f, 0.f, 0.f, 0.f};
+            pv[u][1] = live ? p[1] : f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        const int n_here = n_splits - base < 64 ? n_splits - base : 64;
-        for (int s0 = 0; s0 < n_here; s0 += 8) {
-            float2 pv[8];
+        if (base == 0) {
+            m_star = ml.x;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const size_t row = (slot0 + base + s0 + u) * q_rows_pad + r;
-                pv[u] = (s0 + u < n_here && ch < D.d) ? *reinterpret_cast<const float2 *>(a.part_o + row * D.d + ch) : float2{0.f, 0.f};
-            }
+            for (int off = 32; off >= 1; off >>= 1) m_star = fmaxf(m_star, __shfl_xor(m_star, off));
+            w_lane = lane < n_splits ? exp2f(ml.x - m_star) : 0.f;
+        }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float w = __shfl(w_lane, s0 + u);   // lanes past n_here hold 0
-                num0 += w * pv[u].x;
-                num1 += w * pv[u].y;
+        for (int u = 0; u < BATCH; ++u) {
+            const int s = base + 4 * u + sg;
+            const float w = __shfl(w_lane, s < 64 ? s : 0);   // chunks past n_splits carry weight 0
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                num[e] += w * pv[u][0][e];
+                num[4 + e] += w * pv[u][1][e];
             }
         }
     }
+    float den = w_lane * ml.y;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off);
-    if (ch < D.d) {
-        const int j = r / D.g, hl = r % D.g, m = b * (k + 1) + j;
-        const int col = (kvh * D.g + hl) * D.d + ch;
-        uint16_t h0, l0, h1, l1;
-        split_bf16(num0 / den, h0, l0);
-        split_bf16(num1 / den, h1, l1);
-        const size_t idx = packed_index(m, col, KTq);  // col is even: both channels share a lane record
-        a.out_hi[idx] = h0; a.out_hi[idx + 1] = h1;
-        a.out_lo[idx] = l0; a.out_lo[idx + 1] = l1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        num[e] += __shfl_xor(num[e], 16);
+        num[e] += __shfl_xor(num[e], 32);
     }
+    if (sg == 0 && cl < LPR) {
+        const int j = r / D.g, hl = r % D.g, m = b * (k + 1) + j;
+        const int col = (kvh * D.g + hl) * HD + cl * 8;
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            uint16_t h0, l0, h1, l1;
+            split_bf16(num[e] / den, h0, l0);
+            split_bf16(num[e + 1] / den, h1, l1);
+            hi[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            lo[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        const size_t idx = packed_index(m, col, KTq);   // col % 8 == 0: one whole lane record
+        *reinterpret_cast<u32x4 *>(a.out_hi + idx) = u32x4{hi[0], hi[1], hi[2], hi[3]};
+        *reinterpret_cast<u32x4 *>(a.out_lo + idx) = u32x4{lo[0], lo[1], lo[2], lo[3]};
+    }
+}
+
+template <int HD, int NW> void launch_nw(const Dims &D, const AttnArgs &a, int q_rows_pad, int rt0, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((attn_partial_kernel<HD, NW>), grid, dim3(NW * 64), 0, s, D, a, q_rows_pad, rt0);
 }
 
 template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, int q_rows_pad, hipStream_t s)
 {
     const int rows = D.g * (a.k + 1);
     const int rt_total = (rows + 15) / 16;
-    const dim3 grid(D.max_splits, D.nkv, a.B);
-    // Up to 3 query-row tiles per wave; more rows take further passes over the cache.
-    for (int rt0 = 0; rt0 < rt_total; rt0 += 3) {
-        const int rt = rt_total - rt0 < 3 ? rt_total - rt0 : 3;
-        switch (rt) {
-        case 1: hipLaunchKernelGGL((attn_partial_kernel<HD, 1>), grid, dim3(64), 0, s, D, a, q_rows_pad, rt0); break;
-        case 2: hipLaunchKernelGGL((attn_partial_kernel<HD, 2>), grid, dim3(64), 0, s, D, a, q_rows_pad, rt0); break;
-        default: hipLaunchKernelGGL((attn_partial_kernel<HD, 3>), grid, dim3(64), 0, s, D, a, q_rows_pad, rt0); break;
+    const dim3 grid(a.n_splits, D.nkv, a.B);
+    // One wave per query-row tile; more than MAX_WAVES tiles take further passes over the cache.
+    for (int rt0 = 0; rt0 < rt_total; rt0 += MAX_WAVES) {
+        const int nw = rt_total - rt0 < MAX_WAVES ? rt_total - rt0 : MAX_WAVES;
+        switch (nw) {
+        case 1: launch_nw<HD, 1>(D, a, q_rows_pad, rt0, grid, s); break;
+        case 2: launch_nw<HD, 2>(D, a, q_rows_pad, rt0, grid, s); break;
+        case 3: launch_nw<HD, 3>(D, a, q_rows_pad, rt0, grid, s); break;
+        case 4: launch_nw<HD, 4>(D, a, q_rows_pad, rt0, grid, s); break;
+        case 5: launch_nw<HD, 5>(D, a, q_rows_pad, rt0, grid, s); break;
+        default: launch_nw<HD, 6>(D, a, q_rows_pad, rt0, grid, s); break;
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -238,12 +288,34 @@ template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, in
 
 }  // namespace
 
-hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s)
+// Positions per workgroup for a step of B sequences: about 2048 workgroups over
+// (sequence, kv head, chunk), whole 32-position blocks, at most 64 chunks per sequence.
+int attention_chunk(const Dims &D, int B)
 {
+    long chunk = ((long)D.seq_pad * B * D.nkv + 2047) / 2048;
+    const long floor64 = (D.seq_pad + 63) / 64;
+    if (chunk < floor64) chunk = floor64;
+    chunk = (chunk + 31) / 32 * 32;
+    if (chunk < 64) chunk = 64;
+    return (int)chunk;
+}
+
+int attention_splits(const Dims &D, int B)
+{
+    const int chunk = attention_chunk(D, B);
+    return (D.seq_pad + chunk - 1) / chunk;
+}
+
+hipError_t launch_attention(const Dims &D, const AttnArgs &a_in, hipStream_t s)
+{
+    AttnArgs a = a_in;
+    a.chunk = attention_chunk(D, a.B);
+    a.n_splits = attention_splits(D, a.B);
     const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
     hipError_t e = D.d == 128 ? launch_partial<128>(D, a, q_rows_pad, s) : launch_partial<64>(D, a, q_rows_pad, s);
     if (e != hipSuccess) return e;
     const int n_tasks = a.B * D.nkv * D.g * (a.k + 1);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3((n_tasks + 3) / 4), dim3(256), 0, s, D, a, q_rows_pad);
+    if (D.d == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, dim3((n_tasks + 3) / 4), dim3(256), 0, s, D, a, q_rows_pad);
+    else hipLaunchKernelGGL(attn_combine_kernel<64>, dim3((n_tasks + 3) / 4), dim3(256), 0, s, D, a, q_rows_pad);
     return hipGetLastError();
 }

@@ -57,7 +57,6 @@ struct Dims {
     int L, h, nq, nkv, d, f, V;
     int qd, kd, g;       // nq*d, nkv*d, nq/nkv
     int max_batch, max_k, max_seq, seq_pad;  // seq_pad = max_seq rounded up to 32
-    int chunk, max_splits;                   // attention: positions per wave, waves per (b, head)
     float eps, rope_base;
 };
 

@@ -81,9 +81,13 @@ struct AttnArgs {
     const uint16_t *Qp_lo;     // bf16 lo part: q ~= hi + lo
     const uint16_t *Kc, *Vc;   // this layer's cache
     const int32_t *pos_base;   // validated lens
-    float *part_o;             // [b][kv head][split][q_rows_pad][d]
-    float *part_ml;            // [b][kv head][split][q_rows_pad][2]  (running max in log2 units, sum)
+    float *part_o;             // [b][kv head][n_splits][q_rows_pad][d]
+    float *part_ml;            // [b][kv head][n_splits][q_rows_pad][2]  (running max in log2 units, sum)
     uint16_t *out_hi, *out_lo; // packed activations for the O projection (K = nq*d)
     int B, k;
+    int chunk, n_splits;       // filled in by launch_attention: positions per workgroup, partial slots per (b, kv head)
 };
+// Positions per workgroup and chunks per sequence for a step of B sequences (sizes the partial buffers).
+int attention_chunk(const Dims &D, int B);
+int attention_splits(const Dims &D, int B);
 hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s);
