@@ -180,7 +180,8 @@ struct Prof {
     hipStream_t s;
     int cls;
     ProfEvent *ev;
-    Prof(sssd_ctx *ctx, hipStream_t st, int k) : c(ctx), s(st), cls(k), ev(nullptr)
+    bool own;   // true: the launch itself stamps the events (kernel start and end), nothing is recorded here
+    Prof(sssd_ctx *ctx, hipStream_t st, int k, bool kernel_stamps = false) : c(ctx), s(st), cls(k), ev(nullptr), own(kernel_stamps)
     {
         if (!c->prof_on) return;
         if (c->prof_used == c->prof_pool.size()) {
@@ -192,11 +193,13 @@ struct Prof {
         }
         ev = &c->prof_pool[c->prof_used++];
         ev->cls = k;
-        (void)hipEventRecord(ev->a, s);
+        if (!own) (void)hipEventRecord(ev->a, s);
     }
+    hipEvent_t start() const { return ev ? ev->a : nullptr; }
+    hipEvent_t stop() const { return ev ? ev->b : nullptr; }
     ~Prof()
     {
-        if (ev) (void)hipEventRecord(ev->b, s);
+        if (ev && !own) (void)hipEventRecord(ev->b, s);
     }
 };
 
@@ -403,8 +406,8 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
     auto fgemm = [&](int epi) -> hipError_t {
         bool more = false;
         {
-            Prof p(c, s, SSSD_PROF_GEMM);
-            hipError_t e = launch_stream_gemm(f, epi, s, &more);
+            Prof p(c, s, SSSD_PROF_GEMM, true);
+            hipError_t e = launch_stream_gemm(f, epi, s, &more, p.start(), p.stop());
             if (e != hipSuccess || !more) return e;
         }
         Prof p(c, s, SSSD_PROF_ELEM);
@@ -576,7 +579,7 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
     a.KT = (K + 31) / 32; a.NT = N / 16; a.n_units = a.NT; a.Ntot = N; a.M = M; a.out = out;
     a.partials = (float *)scratch; a.partial_bytes = scratch_bytes;
     bool more = false;
-    HIP_TRY(launch_stream_gemm(a, FEPI_STORE, (hipStream_t)stream, &more));
+    HIP_TRY(launch_stream_gemm(a, FEPI_STORE, (hipStream_t)stream, &more, nullptr, nullptr));
     if (more) HIP_TRY(launch_stream_epilogue(a, FEPI_STORE, (hipStream_t)stream));
     return SSSD_OK;
 }

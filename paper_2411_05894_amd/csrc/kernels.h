@@ -53,8 +53,10 @@ size_t stream_gemm_partial_bytes(const Dims &D, int M);
 size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-level entry point)
 // Launches the weight-streaming kernel and records its plan (J, part_rows, ...) in `a`; when
 // *needs_epilogue comes back true the results are split-K partials and launch_stream_epilogue
-// must follow with the same `a`.
-hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue);
+// must follow with the same `a`.  With t0/t1 non-null the dispatch stamps them at the kernel's own
+// start and end (what a profiler reports as the kernel's duration).
+hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,
+                              hipEvent_t t1);
 hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
                               uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,

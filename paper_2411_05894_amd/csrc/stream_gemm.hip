@@ -32,6 +32,8 @@
 // which commutes with the matrix product.
 #include "kernels.h"
 
+#include <hip/hip_ext.h>
+
 namespace {
 
 __device__ __forceinline__ f32x4 mfma(const u32x4 &a, const u32x4 &b, f32x4 c)
@@ -476,7 +478,7 @@ __host__ QPlan q_plan(int Ntot, int K)
     return p;
 }
 
-template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue)
+template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue, hipEvent_t t0, hipEvent_t t1)
 {
     *needs_epilogue = true;
     const int NT16 = a.Ntot / 16;
@@ -491,12 +493,13 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool
     const dim3 grid(p.groups * a.J), block(QW * 64);
     for (int m_base = 0; m_base < a.M; m_base += 160) {
         const int mt32 = (a.M - m_base + 31) / 32;
+        hipEvent_t e0 = m_base == 0 ? t0 : nullptr, e1 = m_base + 160 >= a.M ? t1 : nullptr;   // first pass starts, last pass stops
         switch (mt32 > 5 ? 5 : mt32) {
-        case 1: hipLaunchKernelGGL((qgemm_kernel<1>), grid, block, 0, s, a, m_base, NT16); break;
-        case 2: hipLaunchKernelGGL((qgemm_kernel<2>), grid, block, 0, s, a, m_base, NT16); break;
-        case 3: hipLaunchKernelGGL((qgemm_kernel<3>), grid, block, 0, s, a, m_base, NT16); break;
-        case 4: hipLaunchKernelGGL((qgemm_kernel<4>), grid, block, 0, s, a, m_base, NT16); break;
-        default: hipLaunchKernelGGL((qgemm_kernel<5>), grid, block, 0, s, a, m_base, NT16); break;
+        case 1: hipExtLaunchKernelGGL((qgemm_kernel<1>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); break;
+        case 2: hipExtLaunchKernelGGL((qgemm_kernel<2>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); break;
+        case 3: hipExtLaunchKernelGGL((qgemm_kernel<3>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); break;
+        case 4: hipExtLaunchKernelGGL((qgemm_kernel<4>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); break;
+        default: hipExtLaunchKernelGGL((qgemm_kernel<5>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); break;
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -504,7 +507,7 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool
     return hipSuccess;
 }
 
-template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue)
+template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue, hipEvent_t t0, hipEvent_t t1)
 {
     // k-tiles per wave: 7 when K is a multiple of 16*7*32 but not of 16*8*32 (the FFN widths of the
     // Llama shapes), else 8; a ragged K split is legal either way.
@@ -518,8 +521,8 @@ template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool
     const int groups = (a.n_units + a.upw - 1) / a.upw;
     a.part_rows = 16;
     if (a.J > 1 && (size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
-    if (seven) hipLaunchKernelGGL((pgemm_kernel<EPI, 7>), dim3(groups * a.J), dim3(PW * 64), 0, s, a);
-    else hipLaunchKernelGGL((pgemm_kernel<EPI, 8>), dim3(groups * a.J), dim3(PW * 64), 0, s, a);
+    if (seven) hipExtLaunchKernelGGL((pgemm_kernel<EPI, 7>), dim3(groups * a.J), dim3(PW * 64), 0, s, t0, t1, 0, a);
+    else hipExtLaunchKernelGGL((pgemm_kernel<EPI, 8>), dim3(groups * a.J), dim3(PW * 64), 0, s, t0, t1, 0, a);
     *needs_epilogue = a.J > 1;
     return hipGetLastError();
 }
@@ -572,23 +575,24 @@ size_t stream_gemm_scratch_bytes(int M, int N, int K)
     return j > 1 ? j * 16 * N * sizeof(float) : 0;
 }
 
-hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue)
+hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,
+                              hipEvent_t t1)
 {
     if (a.M > stream_gemm_max_rows()) {
         switch (epilogue) {
-        case FEPI_QKV: return launch_large<FEPI_QKV>(a, s, needs_epilogue);
-        case FEPI_RESID: return launch_large<FEPI_RESID>(a, s, needs_epilogue);
-        case FEPI_SWIGLU: return launch_large<FEPI_SWIGLU>(a, s, needs_epilogue);
-        case FEPI_STORE: return launch_large<FEPI_STORE>(a, s, needs_epilogue);
-        default: return launch_large<FEPI_LM>(a, s, needs_epilogue);
+        case FEPI_QKV: return launch_large<FEPI_QKV>(a, s, needs_epilogue, t0, t1);
+        case FEPI_RESID: return launch_large<FEPI_RESID>(a, s, needs_epilogue, t0, t1);
+        case FEPI_SWIGLU: return launch_large<FEPI_SWIGLU>(a, s, needs_epilogue, t0, t1);
+        case FEPI_STORE: return launch_large<FEPI_STORE>(a, s, needs_epilogue, t0, t1);
+        default: return launch_large<FEPI_LM>(a, s, needs_epilogue, t0, t1);
         }
     }
     switch (epilogue) {
-    case FEPI_QKV: return launch_small<FEPI_QKV>(a, s, needs_epilogue);
-    case FEPI_RESID: return launch_small<FEPI_RESID>(a, s, needs_epilogue);
-    case FEPI_SWIGLU: return launch_small<FEPI_SWIGLU>(a, s, needs_epilogue);
-    case FEPI_STORE: return launch_small<FEPI_STORE>(a, s, needs_epilogue);
-    default: return launch_small<FEPI_LM>(a, s, needs_epilogue);
+    case FEPI_QKV: return launch_small<FEPI_QKV>(a, s, needs_epilogue, t0, t1);
+    case FEPI_RESID: return launch_small<FEPI_RESID>(a, s, needs_epilogue, t0, t1);
+    case FEPI_SWIGLU: return launch_small<FEPI_SWIGLU>(a, s, needs_epilogue, t0, t1);
+    case FEPI_STORE: return launch_small<FEPI_STORE>(a, s, needs_epilogue, t0, t1);
+    default: return launch_small<FEPI_LM>(a, s, needs_epilogue, t0, t1);
     }
 }
 
