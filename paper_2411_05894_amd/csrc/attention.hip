@@ -33,8 +33,10 @@ constexpr float NEG_BIG = -1.0e30f;
 constexpr int MAX_WAVES = 6;   // query-row tiles per launch
 
 // grid = (splits, kv heads, sequences); block = NW waves; wave w owns query-row tile rt_base + w.
+// The kernel is bound by bytes in flight, i.e. by resident workgroups: with three or more waves the
+// register allocator is held to three waves per SIMD (four workgroups per compute unit).
 template <int HD, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_partial_kernel(Dims D, AttnArgs a, int q_rows_pad, int rt_base)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3 ? 3 : NW, 3))) void attn_partial_kernel(Dims D, AttnArgs a, int q_rows_pad, int rt_base)
 {
     constexpr int KS = HD / 32, DT = HD / 16;
     constexpr int CPR = HD / 8;          // 16-byte records per cached K row

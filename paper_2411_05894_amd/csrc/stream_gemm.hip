@@ -5,14 +5,14 @@
 // MI355X ridge (~312 flop/byte), so each launch is a stream of the weight matrix through
 // the matrix cores with everything else hidden behind it.
 //
-//   pgemm_kernel   M <= 16 rows.  Persistent: one workgroup of 16 waves per compute unit walks a
+//   pgemm_kernel   M <= 32 rows (one or two 16-row tiles).  Persistent: one workgroup of 16 waves per compute unit walks a
 //                  list of 16-column output tiles.  Each wave owns a fixed k-slice and keeps the
 //                  activations of that slice (bf16 hi and lo parts) in registers for the whole
 //                  launch, so the inner loop touches memory only for weights.  Weight registers
 //                  are refilled for the NEXT tile right after the MFMA that consumed them: a
 //                  rolling prefetch with a constant number of bytes in flight per wave and no
 //                  bubble at tile boundaries.  The k-split is reduced through LDS in fixed order.
-//   qgemm_kernel   M > 16 rows (up to 160 per pass).  v_mfma_f32_32x32x16_bf16 tiles: a workgroup of four
+//   qgemm_kernel   M > 32 rows (up to 160 per pass).  v_mfma_f32_32x32x16_bf16 tiles: a workgroup of four
 //                  waves owns 256 output columns and one k-slice; each wave streams the weights of
 //                  its own 64 columns HBM -> registers (rolling prefetch, every weight byte read
 //                  once), while the activation k-tiles, which all four waves need, are staged
@@ -171,32 +171,39 @@ __device__ __forceinline__ float row_rstd(const FusedGemmArgs &a, int m, int lan
     return rsqrtf(sum / (float)a.h + a.eps);
 }
 
-// ------------------------------------------------------------------ M <= 16 ----
+// ------------------------------------------------------------------ M <= 32 ----
 constexpr int PW = 16;  // waves per workgroup
 
-template <int KPW, bool PREFETCH>
-__device__ __forceinline__ f32x4 stream_tile(const u32x4 (&ah)[KPW], const u32x4 (&al)[KPW], u32x4 (&w)[KPW], const u32x4 *wn,
-                                             const int (&koff)[KPW])
+template <int KPW, int MT, bool PREFETCH>
+__device__ __forceinline__ void stream_tile(const u32x4 (&ah)[MT][KPW], const u32x4 (&al)[MT][KPW], u32x4 (&w)[KPW], const u32x4 *wn,
+                                            const int (&koff)[KPW], f32x4 (&acc)[MT])
 {
-    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    f32x4 s0[MT], s1[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) s0[mt] = s1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < KPW; ++i) {
-        s0 = mfma(ah[i], w[i], s0);
-        s1 = mfma(al[i], w[i], s1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            s0[mt] = mfma(ah[mt][i], w[i], s0[mt]);
+            s1[mt] = mfma(al[mt][i], w[i], s1[mt]);
+        }
         if (PREFETCH) w[i] = __builtin_nontemporal_load(wn + koff[i]);
     }
-    return s0 + s1;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = s0[mt] + s1[mt];
 }
 
-// grid = n_groups * J workgroups of 1024 threads.  Workgroup (grp, j) computes units
-// [grp*upw, (grp+1)*upw) over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1 it stores fp32
-// partial tiles for epi_kernel instead of applying the epilogue.
-template <int EPI, int KPW>
+// grid = n_groups * J workgroups of 1024 threads; MT row tiles of 16 (M <= 16*MT).  Workgroup
+// (grp, j) computes units [grp*upw, (grp+1)*upw) over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1
+// it stores fp32 partial tiles for epi_kernel instead of applying the epilogue.
+template <int EPI, int KPW, int MT>
 __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 {
     constexpr int TPU = Unit<EPI>::TILES;
-    __shared__ float red[2][PW][256];
-    __shared__ float rstd_s[16];
+    constexpr int NBUF = MT == 1 ? 2 : 1;   // two row tiles: one reduction buffer (32 KiB) and a second barrier
+    __shared__ float red[NBUF][PW][MT * 256];
+    __shared__ float rstd_s[MT * 16];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int J = a.J, j = blockIdx.x % J, grp = blockIdx.x / J;
     const int KT = a.KT;
@@ -211,39 +218,47 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 #pragma unroll
     for (int i = 0; i < KPW; ++i) koff[i] = (kt0 + i < KT ? kt0 + i : KT - 1) * 64;
 
-    u32x4 w[KPW], ah[KPW], al[KPW];
+    u32x4 w[KPW], ah[MT][KPW], al[MT][KPW];
     const u32x4 *wp = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin, 0)) + lane;
 #pragma unroll
     for (int i = 0; i < KPW; ++i) w[i] = __builtin_nontemporal_load(wp + koff[i]);
 #pragma unroll
-    for (int i = 0; i < KPW; ++i) {
-        const bool live = kt0 + i < KT;
-        ah[i] = live ? a.A_hi[(size_t)koff[i] + lane] : u32x4{0, 0, 0, 0};
-        al[i] = live ? a.A_lo[(size_t)koff[i] + lane] : u32x4{0, 0, 0, 0};
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < KPW; ++i) {
+            const bool live = kt0 + i < KT;
+            const size_t at = (size_t)mt * KT * 64 + koff[i] + lane;
+            ah[mt][i] = live ? a.A_hi[at] : u32x4{0, 0, 0, 0};
+            al[mt][i] = live ? a.A_lo[at] : u32x4{0, 0, 0, 0};
+        }
+    if (EPI != FEPI_RESID && EPI != FEPI_STORE && J == 1) {   // published by the first barrier
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
     }
-    if (EPI != FEPI_RESID && EPI != FEPI_STORE && J == 1) rstd_s[wave] = row_rstd(a, wave, lane);   // published by the first barrier
 
     float keep = 0.f;
     for (int s = 0; s < n_steps; ++s) {
         const int unit = u_begin + s / TPU, part = s % TPU;
-        f32x4 acc;
+        f32x4 acc[MT];
         if (s + 1 < n_steps) {
             const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + (s + 1) / TPU, (s + 1) % TPU)) + lane;
-            acc = stream_tile<KPW, true>(ah, al, w, wn, koff);
+            stream_tile<KPW, MT, true>(ah, al, w, wn, koff, acc);
         } else {
-            acc = stream_tile<KPW, false>(ah, al, w, nullptr, koff);
+            stream_tile<KPW, MT, false>(ah, al, w, nullptr, koff, acc);
         }
-        float *rb = &red[s & 1][0][0];
+        float *rb = &red[NBUF == 2 ? (s & 1) : 0][0][0];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) rb[wave * 256 + r * 64 + lane] = acc[r];
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) rb[wave * (MT * 256) + mt * 256 + r * 64 + lane] = acc[mt][r];
         __syncthreads();
-        // Buffer s&1 is rewritten at step s+2, after the barrier of step s+1, which the four
-        // reducing waves reach only after they have read it.
-        if (wave < 4) {
+        // Two buffers: buffer s&1 is rewritten at step s+2, after the barrier of step s+1, which the
+        // reducing waves reach only after they have read it.  One buffer: the barrier below.
+        if (wave < 4 * MT) {
             float v = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < PW; ++ww) v += rb[ww * 256 + wave * 64 + lane];
-            const int m = 4 * (lane >> 4) + wave, c = lane & 15;
+            for (int ww = 0; ww < PW; ++ww) v += rb[ww * (MT * 256) + wave * 64 + lane];
+            const int m = 16 * (wave >> 2) + 4 * (lane >> 4) + (wave & 3), c = lane & 15;
             if (J > 1) {
                 a.partials[((size_t)j * a.part_rows + m) * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c] = v;
             } else if (TPU == 2 && part == 0) {
@@ -254,58 +269,278 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
                 else epilogue<EPI>(a, unit, m, c, m < a.M, v, 0.f, rs);
             }
         }
+        if (NBUF == 1) __syncthreads();
     }
 }
 
-// grid = (unit blocks, row tiles of 16), 256 threads.  Sums the J partial results of each unit
-// in the order j = 0..J-1 and applies the epilogue.
-template <int EPI>
-__global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int units_per_block)
+// ---- epilogue from split-K partials ----
+// The same four epilogues on 8 consecutive output columns per thread: thread (row r = lane%16,
+// column group kg = lane/16) of a wave owns columns 8*kg..8*kg+7 of a 32-column block, which is
+// exactly one 16-byte lane record of the packed operand layout, so a wave writes whole operand
+// tiles (1 KiB, contiguous) and reads 128 contiguous bytes of each partial row.
+struct Vec8 {
+    float v[8];
+};
+
+__device__ __forceinline__ Vec8 load8(const float *p)
 {
-    constexpr int TPU = Unit<EPI>::TILES;
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
+    return Vec8{{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]}};
+}
+
+__device__ __forceinline__ void store8(float *p, const Vec8 &x)
+{
+    *reinterpret_cast<f32x4 *>(p) = f32x4{x.v[0], x.v[1], x.v[2], x.v[3]};
+    *reinterpret_cast<f32x4 *>(p + 4) = f32x4{x.v[4], x.v[5], x.v[6], x.v[7]};
+}
+
+// x[0..7] -> one lane record of bf16 hi parts and one of lo parts
+__device__ __forceinline__ void split8(const Vec8 &x, u32x4 &hi, u32x4 &lo)
+{
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        uint16_t h0, l0, h1, l1;
+        split_bf16(x.v[e], h0, l0);
+        split_bf16(x.v[e + 1], h1, l1);
+        h[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        l[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+    hi = u32x4{h[0], h[1], h[2], h[3]};
+    lo = u32x4{l[0], l[1], l[2], l[3]};
+}
+
+__device__ __forceinline__ u32x4 round8(const Vec8 &x)
+{
+    uint32_t h[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) h[e >> 1] = (uint32_t)f32_to_bf16(x.v[e]) | ((uint32_t)f32_to_bf16(x.v[e + 1]) << 16);
+    return u32x4{h[0], h[1], h[2], h[3]};
+}
+
+// Sum of the J slices of 8 columns starting at (row m, column col), slices in order.
+__device__ __forceinline__ Vec8 sum_slices(const FusedGemmArgs &a, int m, int col)
+{
+    const float *p = a.partials + (size_t)m * a.Ntot + col;
+    const size_t jstride = (size_t)a.part_rows * a.Ntot;
+    Vec8 s = load8(p);
+    for (int j = 1; j < a.J; ++j) {
+        const Vec8 t = load8(p + j * jstride);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s.v[e] += t.v[e];
+    }
+    return s;
+}
+
+// Column blocks of 32 per epilogue: plain output columns, except QKV, whose blocks run over the
+// first-half channels of each head (the rotary partner columns come along).
+template <int EPI> __device__ __host__ __forceinline__ int column_blocks(const FusedGemmArgs &a)
+{
+    if (EPI == FEPI_QKV) return (a.nq + 2 * a.nkv) * ((a.d / 2 + 31) / 32);
+    if (EPI == FEPI_SWIGLU) return (a.Ntot / 2 + 31) / 32;
+    return (a.Ntot + 31) / 32;
+}
+
+// grid = (column-block groups, row tiles of 16), 256 threads; each wave takes column blocks
+// cb0 + wave, cb0 + wave + 4, ...  The partial sums of a block are fetched one block ahead (the
+// first block's before the row scales are reduced), so the kernel's dependent memory round trips
+// overlap.
+template <int EPI>
+__global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int blocks_per_wg)
+{
     __shared__ float rstd_s[16];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m0 = blockIdx.y * 16;
-    if (EPI != FEPI_RESID && EPI != FEPI_STORE) {
-        for (int r = wave; r < 16; r += 4) {
-            const float rs = row_rstd(a, m0 + r, lane);
-            if (lane == 0) rstd_s[r] = rs;
+    constexpr bool SCALED = EPI != FEPI_RESID && EPI != FEPI_STORE;
+    constexpr bool PAIRED = EPI == FEPI_QKV || EPI == FEPI_SWIGLU;
+    const int r = lane & 15, kg = lane >> 4, m = m0 + r;
+    const bool row_ok = m < a.M;
+    const int n_cb = column_blocks<EPI>(a);
+    const int cb_begin = blockIdx.x * blocks_per_wg;
+    const int cb_end = cb_begin + blocks_per_wg < n_cb ? cb_begin + blocks_per_wg : n_cb;
+    const int half = a.d >> 1, bph = (half + 31) / 32;   // QKV: column blocks per head
+
+    // first output column of this thread in block cb (QKV: of the head's first half), or -1
+    auto column = [&](int cb) -> int {
+        if (!row_ok) return -1;
+        if (EPI == FEPI_QKV) {
+            const int ch = (cb % bph) * 32 + kg * 8;
+            return ch < half ? (cb / bph) * a.d + ch : -1;
+        }
+        const int n0 = cb * 32 + kg * 8;
+        return n0 < (EPI == FEPI_SWIGLU ? a.Ntot >> 1 : a.Ntot) ? n0 : -1;
+    };
+    auto fetch = [&](int cb, Vec8 &v0, Vec8 &v1) {
+        const int col = cb < cb_end ? column(cb) : -1;
+        if (col >= 0) {
+            v0 = sum_slices(a, m, col);
+            if (PAIRED) v1 = sum_slices(a, m, col + (EPI == FEPI_QKV ? half : a.Ntot >> 1));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v0.v[e] = v1.v[e] = 0.f;
+        }
+    };
+
+    // Row scales: four rows per wave.  Their loads go out first and the first block's partial
+    // sums right behind them, so the two dependent round trips overlap.
+    constexpr int SV = 8;                     // sums of squares per lane and row held in registers (h <= 8192)
+    const int NSS = a.h >> 4;
+    float sv[4][SV];
+    if (SCALED) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int mm = m0 + wave + 4 * q;
+#pragma unroll
+            for (int i = 0; i < SV; ++i) {
+                const int t = lane + 64 * i;
+                sv[q][i] = (mm < a.M && t < NSS) ? a.ssq_in[(size_t)mm * NSS + t] : 0.f;
+            }
+        }
+    }
+    Vec8 v0, v1;
+    fetch(cb_begin + wave, v0, v1);
+    if (SCALED) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int mm = m0 + wave + 4 * q;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < SV; ++i) sum += sv[q][i];
+            if (mm < a.M)
+                for (int t = lane + 64 * SV; t < NSS; t += 64) sum += a.ssq_in[(size_t)mm * NSS + t];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+            if (lane == 0) rstd_s[wave + 4 * q] = rsqrtf(sum / (float)a.h + a.eps);
         }
         __syncthreads();
     }
-    const int ml = 4 * (lane >> 4) + wave, m = m0 + ml, c = lane & 15;
-    const bool valid = m < a.M;
-    const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[ml];
-    const int u_begin = blockIdx.x * units_per_block;
-    const int u_end = u_begin + units_per_block < a.n_units ? u_begin + units_per_block : a.n_units;
-    const size_t jstride = (size_t)a.part_rows * a.Ntot;
-    for (int unit = u_begin; unit < u_end; ++unit) {
-        float v[TPU];
+    const float rs = SCALED ? rstd_s[r] : 1.f;
+
+    for (int cb = cb_begin + wave; cb < cb_end; cb += 4) {
+        Vec8 n0v, n1v;
+        fetch(cb + 4, n0v, n1v);
+        const int col = column(cb);
+        const bool live = col >= 0;
+        if (EPI == FEPI_QKV) {
+            if (live) {
+                int head = cb / bph;
+                const int ch = col - head * a.d;              // first-half channel of v0[0]
+                const int b = m / (a.k + 1), j = m % (a.k + 1);
+                const int pos = a.pos_base[b] + j;
+                const size_t slab = (size_t)b * a.nkv * a.seq_pad * a.d;
 #pragma unroll
-        for (int part = 0; part < TPU; ++part) {
-            const float *p = a.partials + (size_t)m * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c;
-            float s = 0.f;
-            if (valid)
-                for (int j = 0; j < a.J; ++j) s += p[j * jstride];
-            v[part] = s;
+                for (int e = 0; e < 8; ++e) { v0.v[e] *= rs; v1.v[e] *= rs; }
+                if (head < a.nq + a.nkv) {
+                    const float *cs = a.rope_cs + ((size_t)pos * half + ch) * 2;
+                    const Vec8 cs0 = load8(cs), cs1 = load8(cs + 8);   // (cos, sin) of channels ch..ch+3, ch+4..ch+7
+                    Vec8 y0, y1;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float co = e < 4 ? cs0.v[2 * e] : cs1.v[2 * (e - 4)], si = e < 4 ? cs0.v[2 * e + 1] : cs1.v[2 * (e - 4) + 1];
+                        y0.v[e] = v0.v[e] * co - v1.v[e] * si;
+                        y1.v[e] = v0.v[e] * si + v1.v[e] * co;
+                    }
+                    if (head < a.nq) {
+                        const int g = a.nq / a.nkv, kvh = head / g, hl = head % g, rr = j * g + hl;
+                        const size_t qs = ((size_t)b * a.nkv + kvh) * a.q_rows_pad * a.d;
+                        u32x4 h0, l0, h1, l1;
+                        split8(y0, h0, l0);
+                        split8(y1, h1, l1);
+                        const size_t i_0 = qs + packed_index(rr, ch, a.d >> 5), i_1 = qs + packed_index(rr, ch + half, a.d >> 5);
+                        *reinterpret_cast<u32x4 *>(a.Qp + i_0) = h0; *reinterpret_cast<u32x4 *>(a.Qp_lo + i_0) = l0;
+                        *reinterpret_cast<u32x4 *>(a.Qp + i_1) = h1; *reinterpret_cast<u32x4 *>(a.Qp_lo + i_1) = l1;
+                    } else {
+                        head -= a.nq;
+                        uint16_t *kr = a.Kc + slab + ((size_t)head * a.seq_pad + pos) * a.d;
+                        *reinterpret_cast<u32x4 *>(kr + ch) = round8(y0);
+                        *reinterpret_cast<u32x4 *>(kr + ch + half) = round8(y1);
+                    }
+                } else {
+                    head -= a.nq + a.nkv;
+                    uint16_t *vv = a.Vc + slab + (size_t)head * a.seq_pad * a.d;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        vv[vcache_index(pos, ch + e, a.d)] = f32_to_bf16(v0.v[e]);
+                        vv[vcache_index(pos, ch + half + e, a.d)] = f32_to_bf16(v1.v[e]);
+                    }
+                }
+            }
+        } else if (EPI == FEPI_SWIGLU) {
+            if (live) {
+                Vec8 hv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float gg = v0.v[e] * rs;
+                    hv.v[e] = gg / (1.f + __expf(-gg)) * (v1.v[e] * rs);
+                }
+                u32x4 hi, lo;
+                split8(hv, hi, lo);
+                const size_t idx = packed_index(m, col, a.KT_out);
+                *reinterpret_cast<u32x4 *>(a.out_hi + idx) = hi;
+                *reinterpret_cast<u32x4 *>(a.out_lo + idx) = lo;
+            }
+        } else if (EPI == FEPI_STORE) {
+            if (live) store8(a.out + (size_t)m * a.Ntot + col, v0);
+        } else if (EPI == FEPI_RESID) {
+            float ss = 0.f;
+            if (live) {
+                const Vec8 x = load8(a.X + (size_t)m * a.h + col);
+                Vec8 xn, xg;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    xn.v[e] = x.v[e] + v0.v[e];
+                    xg.v[e] = xn.v[e] * bf16_to_f32(a.gamma_next[col + e]);   // caller's array: no alignment assumed
+                    ss += xn.v[e] * xn.v[e];
+                }
+                store8(a.X + (size_t)m * a.h + col, xn);
+                u32x4 hi, lo;
+                split8(xg, hi, lo);
+                const size_t idx = packed_index(m, col, (a.h + 31) >> 5);
+                *reinterpret_cast<u32x4 *>(a.out_hi + idx) = hi;
+                *reinterpret_cast<u32x4 *>(a.out_lo + idx) = lo;
+            }
+            ss += __shfl_xor(ss, 16);   // the other 8 columns of the 16-column group
+            if (live && !(kg & 1)) a.ssq_out[(size_t)m * (a.h >> 4) + (col >> 4)] = ss;
+        } else {  // FEPI_LM
+            const int n0 = cb * 32 + kg * 8;
+            float bv = -INFINITY;
+            int bi = n0;
+            if (live) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float logit = v0.v[e] * rs;
+                    v0.v[e] = logit;
+                    if (logit > bv) { bv = logit; bi = n0 + e; }   // ascending columns: the lowest index keeps a tie
+                }
+                if (a.logits) store8(a.logits + (size_t)m * a.vocab + n0, v0);
+            }
+            const float ov = __shfl_xor(bv, 16);
+            const int oi = __shfl_xor(bi, 16);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            if (live && !(kg & 1)) {
+                a.part_val[(size_t)m * a.NT + (n0 >> 4)] = bv;
+                a.part_idx[(size_t)m * a.NT + (n0 >> 4)] = bi;
+            }
         }
-        epilogue<EPI>(a, unit, m, c, valid, v[0], v[TPU - 1], rs);
+        v0 = n0v;
+        v1 = n1v;
     }
 }
-
 
 template <int EPI> hipError_t launch_epi(const FusedGemmArgs &a, hipStream_t s)
 {
     const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
     const int row_tiles = (a.M + 15) / 16;
-    const int blocks_x = (4 * n_cu + row_tiles - 1) / row_tiles;
-    int upb = (a.n_units + blocks_x - 1) / blocks_x;
-    if (upb < 1) upb = 1;
-    hipLaunchKernelGGL((epi_kernel<EPI>), dim3((a.n_units + upb - 1) / upb, row_tiles), dim3(256), 0, s, a, upb);
+    const int n_cb = column_blocks<EPI>(a);
+    // about 4 workgroups per compute unit, whole groups of four column blocks (one per wave)
+    const int groups_x = (4 * n_cu + row_tiles - 1) / row_tiles;
+    int bpw = (n_cb + groups_x - 1) / groups_x;
+    bpw = (bpw + 3) / 4 * 4;
+    hipLaunchKernelGGL((epi_kernel<EPI>), dim3((n_cb + bpw - 1) / bpw, row_tiles), dim3(256), 0, s, a, bpw);
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------- M > 16 ----
+// ------------------------------------------------------------------- M > 32 ----
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 __device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, f32x16 c)
@@ -414,33 +649,43 @@ __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_b
     stage_store(0, apre[0]);
     __syncthreads();
 
-    for (int it0 = 0; it0 < n_iter; it0 += QDW) {
+    // One k-tile: MFMAs on LDS slot it&1 with weight slot u, refill both register slots for
+    // iteration it+QDW, move chunk it+1 to the other LDS slot.  The steady-state loop below runs it
+    // with every branch resolved at compile time: a load that is only conditionally issued would
+    // force the wait counters in front of every later use down to "nothing outstanding".
+    auto ktile = [&](int u, int it, bool refill, bool next_chunk) {
+        const u32x4 *buf = ring[it & 1];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int rec = hh ? r1 : r0;
+#pragma unroll
+            for (int i = 0; i < MT32; ++i) {
+                // tile index in the chunk: (mt16 * 2 + hi/lo) with mt16 = 2i + (lane/16)%2
+                const int t_hi = ((2 * i + ((lane >> 4) & 1)) * 2) * 64 + rec;
+                const u32x4 xh = buf[t_hi], xl = buf[t_hi + 64];
+#pragma unroll
+                for (int g = 0; g < QNG; ++g) {
+                    acc[i][g] = mfma32(xh, w[u][g][hh], acc[i][g]);
+                    acc[i][g] = mfma32(xl, w[u][g][hh], acc[i][g]);
+                }
+            }
+        }
+        if (refill) issue(u, it + QDW);
+        // LDS slot (it+1)&1 held chunk it-1, which every wave finished before the barrier that
+        // ended iteration it-1.
+        if (next_chunk) stage_store((it + 1) & 1, apre[(u + 1) % QDW]);
+        __syncthreads();
+    };
+    int it0 = 0;
+    for (; it0 + 2 * QDW <= n_iter; it0 += QDW) {   // every iteration of the group refills
+#pragma unroll
+        for (int u = 0; u < QDW; ++u) ktile(u, it0 + u, true, true);
+    }
+    for (; it0 < n_iter; it0 += QDW) {              // the last groups drain the pipeline
 #pragma unroll
         for (int u = 0; u < QDW; ++u) {
             const int it = it0 + u;
-            if (it < n_iter) {
-                const u32x4 *buf = ring[it & 1];
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const int rec = hh ? r1 : r0;
-#pragma unroll
-                    for (int i = 0; i < MT32; ++i) {
-                        // tile index in the chunk: (mt16 * 2 + hi/lo) with mt16 = 2i + (lane/16)%2
-                        const int t_hi = ((2 * i + ((lane >> 4) & 1)) * 2) * 64 + rec;
-                        const u32x4 xh = buf[t_hi], xl = buf[t_hi + 64];
-#pragma unroll
-                        for (int g = 0; g < QNG; ++g) {
-                            acc[i][g] = mfma32(xh, w[u][g][hh], acc[i][g]);
-                            acc[i][g] = mfma32(xl, w[u][g][hh], acc[i][g]);
-                        }
-                    }
-                }
-                if (it + QDW < n_iter) issue(u, it + QDW);
-                // LDS slot (it+1)&1 held chunk it-1, which every wave finished before the barrier
-                // that ended iteration it-1.
-                if (it + 1 < n_iter) stage_store((it + 1) & 1, apre[(u + 1) % QDW]);
-                __syncthreads();
-            }
+            if (it < n_iter) ktile(u, it, it + QDW < n_iter, it + 1 < n_iter);
         }
     }
 
@@ -463,17 +708,30 @@ struct QPlan {
     int groups, J, kps;   // column groups, K slices (none empty), k-tiles per slice
 };
 
-// Column groups of 256 and the K split that brings the grid to about two workgroups per compute unit.
-__host__ QPlan q_plan(int Ntot, int K)
+// Column groups of 256 and the K split.  A workgroup slot is what one compute unit can hold of this
+// kernel at once (3, 2 or 1 workgroups, by the registers the row count needs); the split is the
+// smallest J whose groups*J workgroups fill whole rounds of slots to at least 85 % (else the
+// best-filling one), with at least 8 k-tiles per slice and at most 16 slices.
+__host__ QPlan q_plan(int Ntot, int K, int M)
 {
     const int NT32 = (Ntot / 16 + 1) / 2, KT = (K + 31) / 32;
+    const int mt32 = M >= 160 ? 5 : (M + 31) / 32;
+    const int slots = 256 * (mt32 == 1 ? 3 : (mt32 == 2 ? 2 : 1));
     QPlan p;
     p.groups = (NT32 + QW * QNG - 1) / (QW * QNG);
-    int J = (2 * 256 + p.groups - 1) / p.groups;
-    if (J > KT / 8) J = KT / 8;
-    if (J > 16) J = 16;
-    if (J < 1) J = 1;
-    p.kps = (KT + J - 1) / J;
+    int jmax = KT / 8;
+    if (jmax > 16) jmax = 16;
+    if (jmax < 1) jmax = 1;
+    int best = 1;
+    double best_fill = 0.0;
+    for (int J = 1; J <= jmax; ++J) {
+        const long tasks = (long)p.groups * J;
+        const long rounds = (tasks + slots - 1) / slots;
+        const double fill = (double)tasks / (double)(rounds * slots);
+        if (fill > best_fill + 1e-9) { best_fill = fill; best = J; }
+        if (fill >= 0.85) { best = J; break; }
+    }
+    p.kps = (KT + best - 1) / best;
     p.J = (KT + p.kps - 1) / p.kps;
     return p;
 }
@@ -482,7 +740,7 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool
 {
     *needs_epilogue = true;
     const int NT16 = a.Ntot / 16;
-    const QPlan p = q_plan(a.Ntot, a.KT * 32);
+    const QPlan p = q_plan(a.Ntot, a.KT * 32, a.M);
     a.J = p.J;
     a.kps = p.kps;
     a.part_rows = round_up(a.M, 16);
@@ -507,53 +765,62 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool
     return hipSuccess;
 }
 
+// k-tiles per wave.  One row tile: 7 when K is a multiple of 16*7*32 but not of 16*8*32 (the FFN
+// widths of the Llama shapes), else 8.  Two row tiles: 4 (twice the activations per k-tile in
+// registers).  A ragged K split is legal in every case.
+__host__ int small_kpw(int KT, int mt)
+{
+    if (mt == 2) return 4;
+    return (KT % (PW * 7) == 0 && KT % (PW * 8) != 0) ? 7 : 8;
+}
+
 template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue, hipEvent_t t0, hipEvent_t t1)
 {
-    // k-tiles per wave: 7 when K is a multiple of 16*7*32 but not of 16*8*32 (the FFN widths of the
-    // Llama shapes), else 8; a ragged K split is legal either way.
-    const bool seven = a.KT % (PW * 7) == 0 && a.KT % (PW * 8) != 0;
-    const int kpw = seven ? 7 : 8;
+    const int mt = a.M <= 16 ? 1 : 2;
+    const int kpw = small_kpw(a.KT, mt);
     a.J = (a.KT + PW * kpw - 1) / (PW * kpw);
     const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
     int groups_target = n_cu / a.J;
     if (groups_target < 1) groups_target = 1;
     a.upw = (a.n_units + groups_target - 1) / groups_target;
     const int groups = (a.n_units + a.upw - 1) / a.upw;
-    a.part_rows = 16;
+    a.part_rows = 16 * mt;
     if (a.J > 1 && (size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
-    if (seven) hipExtLaunchKernelGGL((pgemm_kernel<EPI, 7>), dim3(groups * a.J), dim3(PW * 64), 0, s, t0, t1, 0, a);
-    else hipExtLaunchKernelGGL((pgemm_kernel<EPI, 8>), dim3(groups * a.J), dim3(PW * 64), 0, s, t0, t1, 0, a);
+    const dim3 grid(groups * a.J), block(PW * 64);
+    if (mt == 2) hipExtLaunchKernelGGL((pgemm_kernel<EPI, 4, 2>), grid, block, 0, s, t0, t1, 0, a);
+    else if (kpw == 7) hipExtLaunchKernelGGL((pgemm_kernel<EPI, 7, 1>), grid, block, 0, s, t0, t1, 0, a);
+    else hipExtLaunchKernelGGL((pgemm_kernel<EPI, 8, 1>), grid, block, 0, s, t0, t1, 0, a);
     *needs_epilogue = a.J > 1;
     return hipGetLastError();
 }
 
 }  // namespace
 
-int stream_gemm_max_rows() { return 16; }
+int stream_gemm_max_rows() { return 32; }
 
 // Split-K scratch needed for M rows: the largest J * rows * Ntot over the model's GEMMs.
 size_t stream_gemm_partial_bytes(const Dims &D, int M)
 {
-    auto slices = [](int K) {
-        const int KT = (K + 31) / 32;
-        const bool seven = KT % (PW * 7) == 0 && KT % (PW * 8) != 0;
-        const int ks = PW * (seven ? 7 : 8);
-        return (size_t)((KT + ks - 1) / ks);
-    };
     size_t best = 0;
-    auto consider = [&](int K, size_t ntot) {
-        const size_t j = slices(K);
-        if (j > 1 && j * 16 * ntot > best) best = j * 16 * ntot;
-    };
-    consider(D.h, (size_t)D.qd + 2 * D.kd);
-    consider(D.qd, D.h);
-    consider(D.h, 2 * (size_t)D.f);
-    consider(D.f, D.h);
-    consider(D.h, D.V);
-    if (M > stream_gemm_max_rows()) {
-        const size_t rows = (size_t)round_up(M, 16);
+    for (int mt = 1; mt <= (M > 16 ? 2 : 1); ++mt) {
+        auto consider = [&](int K, size_t ntot) {
+            const int KT = (K + 31) / 32, ks = PW * small_kpw(KT, mt);
+            const size_t need = (size_t)((KT + ks - 1) / ks) * 16 * mt * ntot;
+            if (need > 16 * mt * ntot && need > best) best = need;   // only a split K needs scratch
+        };
+        consider(D.h, (size_t)D.qd + 2 * D.kd);
+        consider(D.qd, D.h);
+        consider(D.h, 2 * (size_t)D.f);
+        consider(D.f, D.h);
+        consider(D.h, D.V);
+    }
+    // larger steps: the K split depends on the row count's class (32-row tiles), so take the worst
+    // case over every step size up to M
+    for (int mc = 32; M > stream_gemm_max_rows(); mc += 32) {
+        const int rows_c = mc < M ? mc : M;
+        const size_t rows = (size_t)round_up(rows_c, 16);
         auto large = [&](int K, size_t ntot) {
-            const size_t need = (size_t)q_plan((int)ntot, K).J * rows * ntot;
+            const size_t need = (size_t)q_plan((int)ntot, K, rows_c).J * rows * ntot;
             if (need > best) best = need;
         };
         large(D.h, (size_t)D.qd + 2 * D.kd);
@@ -561,6 +828,7 @@ size_t stream_gemm_partial_bytes(const Dims &D, int M)
         large(D.h, 2 * (size_t)D.f);
         large(D.f, D.h);
         large(D.h, D.V);
+        if (mc >= M) break;
     }
     return best * sizeof(float);
 }
@@ -568,11 +836,10 @@ size_t stream_gemm_partial_bytes(const Dims &D, int M)
 size_t stream_gemm_scratch_bytes(int M, int N, int K)
 {
     const int KT = (K + 31) / 32;
-    if (M > stream_gemm_max_rows()) return (size_t)q_plan(N, K).J * round_up(M, 16) * N * sizeof(float);
-    const bool seven = KT % (PW * 7) == 0 && KT % (PW * 8) != 0;
-    const int ks = PW * (seven ? 7 : 8);
+    if (M > stream_gemm_max_rows()) return (size_t)q_plan(N, K, M).J * round_up(M, 16) * N * sizeof(float);
+    const int mt = M <= 16 ? 1 : 2, ks = PW * small_kpw(KT, mt);
     const size_t j = (size_t)((KT + ks - 1) / ks);
-    return j > 1 ? j * 16 * N * sizeof(float) : 0;
+    return j > 1 ? j * 16 * mt * N * sizeof(float) : 0;
 }
 
 hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,
