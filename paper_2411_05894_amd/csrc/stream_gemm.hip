@@ -208,10 +208,15 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
     const int J = a.J, j = blockIdx.x % J, grp = blockIdx.x / J;
     const int KT = a.KT;
     const int kt0 = (j * PW + wave) * KPW;
-    const int u_begin = grp * a.upw;
-    const int u_end = u_begin + a.upw < a.n_units ? u_begin + a.upw : a.n_units;
-    if (u_begin >= u_end) return;
-    const int n_steps = (u_end - u_begin) * TPU;
+    // Units grp, grp + groups, grp + 2*groups, ... so that at any time the workgroups of a launch
+    // read neighbouring tiles (measured 3 % faster on the layer matrices); the LM head, 30 times as
+    // many tiles, measured 3 % faster with a contiguous run of upw units per workgroup.
+    const int groups = gridDim.x / J;
+    constexpr bool RUNS = EPI == FEPI_LM;
+    const int u_begin = RUNS ? grp * a.upw : grp, u_stride = RUNS ? 1 : groups;
+    if (u_begin >= a.n_units) return;
+    const int n_mine = RUNS ? (u_begin + a.upw < a.n_units ? a.upw : a.n_units - u_begin) : (a.n_units - grp + groups - 1) / groups;
+    const int n_steps = n_mine * TPU;
 
     // k-tiles past the matrix (ragged K split) contribute zero activations and re-read the last tile.
     int koff[KPW];
@@ -238,10 +243,10 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 
     float keep = 0.f;
     for (int s = 0; s < n_steps; ++s) {
-        const int unit = u_begin + s / TPU, part = s % TPU;
+        const int unit = u_begin + (s / TPU) * u_stride, part = s % TPU;
         f32x4 acc[MT];
         if (s + 1 < n_steps) {
-            const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + (s + 1) / TPU, (s + 1) % TPU)) + lane;
+            const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + ((s + 1) / TPU) * u_stride, (s + 1) % TPU)) + lane;
             stream_tile<KPW, MT, true>(ah, al, w, wn, koff, acc);
         } else {
             stream_tile<KPW, MT, false>(ah, al, w, nullptr, koff, acc);
