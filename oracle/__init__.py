@@ -118,6 +118,44 @@ def accept(tokens: Sequence[int], that: Sequence[int]):
     return acc.value, nxt.value
 
 
+def attention_row_masked(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, mask: torch.Tensor) -> torch.Tensor:
+    """q fp32 [d]; Kc, Vc bf16 [n_rows, d]; mask uint8 [n_rows] (nonzero = visible)."""
+    d = q.numel()
+    out = torch.empty(d, dtype=torch.float32)
+    m = mask.to(torch.uint8).contiguous()
+    lib().orc_attention_row_masked(_p(q.contiguous().float()), _p(Kc.contiguous()), _p(Vc.contiguous()), _p(m),
+                                   m.numel(), d, _p(out))
+    return out
+
+
+def tree_depths(parents: Sequence[int]) -> List[int]:
+    k = len(parents) - 1
+    par = np.ascontiguousarray(parents, dtype=np.int32)
+    out = np.zeros(k + 1, dtype=np.int32)
+    lib().orc_tree_depths(_p(par), k, _p(out))
+    return out.tolist()
+
+
+def tree_mask(parents: Sequence[int]) -> np.ndarray:
+    k = len(parents) - 1
+    par = np.ascontiguousarray(parents, dtype=np.int32)
+    out = np.zeros((k + 1, k + 1), dtype=np.uint8)
+    lib().orc_tree_mask(_p(par), k, _p(out))
+    return out
+
+
+def accept_tree(tokens: Sequence[int], parents: Sequence[int], that: Sequence[int]):
+    """Returns (accepted_len, next_token, path) with path[0] = 0."""
+    k = len(tokens) - 1
+    t = np.ascontiguousarray(tokens, dtype=np.int32)
+    par = np.ascontiguousarray(parents, dtype=np.int32)
+    h = np.ascontiguousarray(that, dtype=np.int32)
+    path = np.zeros(k + 1, dtype=np.int32)
+    acc, nxt = C.c_int32(), C.c_int32()
+    lib().orc_accept_tree(_p(t), _p(par), _p(h), k, C.byref(acc), C.byref(nxt), _p(path))
+    return acc.value, nxt.value, path[: acc.value + 1].tolist()
+
+
 def counters_reset():
     lib().orc_counters_reset()
 
@@ -199,6 +237,39 @@ class OracleModel:
         if return_hidden:
             out["hidden"] = x.view(B, sq, -1)
         return out
+
+    def verify_step_tree(self, tokens: torch.Tensor, parents: torch.Tensor, lens: torch.Tensor, compact: bool = True):
+        """The verify pass over draft trees: tokens, parents int [B][k+1] (node 0 = root,
+        parents[b][i] < i; parents[b][0] ignored), lens int [B].  Appends every node's K/V at
+        row lens + node index; with ``compact`` the rows of the accepted path then move to rows
+        lens + 1 .. lens + accepted_len.  Returns logits, ``that``, ``accepted_len``,
+        ``next_token`` and ``path`` (list of node lists)."""
+        B, sq = tokens.shape
+        k = sq - 1
+        assert B <= self.max_batch and int(lens.max()) + sq <= self.max_seq
+        par = parents.to(torch.int32).contiguous()
+        ln = lens.to(torch.int32).contiguous()
+        x = self.embed(tokens)
+        for l in range(self.shape.n_layers):
+            lw = self._lw(l)
+            lib().orc_layer_verify_tree(C.byref(self.cfg), C.byref(lw), _p(x), _p(self.K[l]), _p(self.V[l]),
+                                        _p(ln), _p(par), B, k)
+        logits = self.lm_head(x).view(B, sq, -1)
+        that = torch.empty(B, sq, dtype=torch.int32)
+        acc = torch.empty(B, dtype=torch.int32)
+        nxt = torch.empty(B, dtype=torch.int32)
+        paths = []
+        for b in range(B):
+            for j in range(sq):
+                that[b, j] = argmax(logits[b, j])
+            a, n, path = accept_tree(tokens[b].tolist(), par[b].tolist(), that[b].tolist())
+            acc[b], nxt[b] = a, n
+            paths.append(path)
+            if compact:
+                pa = np.ascontiguousarray(path + [0] * (sq - len(path)), dtype=np.int32)
+                for l in range(self.shape.n_layers):
+                    lib().orc_kv_compact(C.byref(self.cfg), _p(self.K[l]), _p(self.V[l]), b, int(ln[b]), _p(pa), a)
+        return {"logits": logits, "that": that, "accepted_len": acc, "next_token": nxt, "path": paths}
 
     def decode_token(self, b: int, token: int, pos: int) -> torch.Tensor:
         """Plain autoregressive step of sequence ``b``: logits [V] for the token at ``pos``."""

@@ -30,6 +30,11 @@
  * attention closed forms and library routines; attention vs dense masked
  * softmax; RoPE identities; verify pass == sequential single-token decode;
  * acceptance special cases and brute force; speculative loop == greedy loop.
+ * Tree verification (second half of the file): masked attention vs dense
+ * fp64 softmax with the explicit mask; a chain given as a tree == the chain
+ * functions bit for bit; every root-to-node path == sequential decode of that
+ * path; tree acceptance vs enumeration of all root paths; tree speculative
+ * loop == greedy loop including the compacted cache.
  */
 #include <math.h>
 #include <stdint.h>
@@ -331,4 +336,187 @@ void orc_layer_decode_token(const orc_config *c, const orc_layer_weights *w, flo
     orc_linear(gt, 1, c->ffn, w->w_down, h, y);
     for (int i = 0; i < h; ++i) x[i] += y[i];
     free(a); free(q); free(kn); free(vn); free(ao); free(y); free(gt); free(up);
+}
+
+/* ------------------------------------------------------------------------
+ * Tree verification.  The paper verifies a draft TREE, not a chain (Sec. 3.1:
+ * candidates from the input trie and the datastore are merged into a draft
+ * tree, from which "the candidate vector for verification and the
+ * corresponding attention mask" are built); Table 2's attention row carries
+ * that mask explicitly, M of shape (b, s_q, s_kv + s_q), one byte per element.
+ * Node 0 is the root (the last accepted token), parent[i] < i for i = 1..k.
+ * A node sees the old cache, its ancestors and itself; its position is
+ * lens + depth.  Every node's K/V is appended at cache row lens + node index.
+ * ------------------------------------------------------------------------ */
+
+/* depth[0] = 0, depth[i] = depth[parent[i]] + 1 */
+void orc_tree_depths(const int32_t *parent, int k, int32_t *depth)
+{
+    depth[0] = 0;
+    for (int i = 1; i <= k; ++i)
+        depth[i] = depth[parent[i]] + 1;
+}
+
+/* mask[j][i] = 1 iff node i is node j itself or one of its ancestors; [k+1][k+1] */
+void orc_tree_mask(const int32_t *parent, int k, uint8_t *mask)
+{
+    const int sq = k + 1;
+    memset(mask, 0, (size_t)sq * sq);
+    for (int j = 0; j <= k; ++j) {
+        int i = j;
+        for (;;) {
+            mask[(size_t)j * sq + i] = 1;
+            if (i == 0) break;
+            i = parent[i];
+        }
+    }
+}
+
+/* softmax_t(q . k_t / sqrt(d) + M_t) V over rows t = 0 .. n_rows-1, where the
+ * additive mask M_t is 0 for mask[t] != 0 and -infinity otherwise (Table 2,
+ * attention row, with the mask given explicitly). */
+void orc_attention_row_masked(const float *q, const uint16_t *Kc, const uint16_t *Vc,
+                              const uint8_t *mask, int n_rows, int d, float *out)
+{
+    double *p = (double *)malloc(sizeof(double) * (size_t)n_rows);
+    double mx = -INFINITY;
+    for (int t = 0; t < n_rows; ++t) {
+        if (!mask[t]) continue;
+        double s = 0.0;
+        for (int i = 0; i < d; ++i)
+            s += (double)q[i] * (double)orc_bf16_to_f32(Kc[(size_t)t * d + i]);
+        float sf = (float)(s / sqrt((double)d));
+        p[t] = sf;
+        if (p[t] > mx) mx = p[t];
+    }
+    double den = 0.0;
+    for (int t = 0; t < n_rows; ++t) {
+        if (!mask[t]) continue;
+        p[t] = exp(p[t] - mx);
+        den += p[t];
+    }
+    for (int i = 0; i < d; ++i) {
+        double acc = 0.0;
+        for (int t = 0; t < n_rows; ++t)
+            if (mask[t]) acc += p[t] * (double)orc_bf16_to_f32(Vc[(size_t)t * d + i]);
+        out[i] = (float)(acc / den);
+    }
+    free(p);
+}
+
+/* One decoder layer of the verify pass over draft trees; parents is [B][k+1]
+ * (entry 0 of each sequence unused).  Same operations as orc_layer_verify;
+ * only positions (lens + depth) and the attention mask differ. */
+void orc_layer_verify_tree(const orc_config *c, const orc_layer_weights *w, float *x, uint16_t *Kc,
+                           uint16_t *Vc, const int32_t *lens, const int32_t *parents, int B, int k)
+{
+    const int sq = k + 1, M = B * sq, h = c->hidden, d = c->head_dim;
+    const int qd = c->n_q_heads * d, kd = c->n_kv_heads * d, g = c->n_q_heads / c->n_kv_heads;
+    float *a = malloc(sizeof(float) * (size_t)M * h);
+    float *q = malloc(sizeof(float) * (size_t)M * qd);
+    float *kn = malloc(sizeof(float) * (size_t)M * kd);
+    float *vn = malloc(sizeof(float) * (size_t)M * kd);
+    float *ao = malloc(sizeof(float) * (size_t)M * qd);
+    float *y = malloc(sizeof(float) * (size_t)M * h);
+    float *gt = malloc(sizeof(float) * (size_t)M * c->ffn);
+    float *up = malloc(sizeof(float) * (size_t)M * c->ffn);
+    int32_t *depth = malloc(sizeof(int32_t) * (size_t)M);
+    uint8_t *tmask = malloc((size_t)B * sq * sq);
+    for (int b = 0; b < B; ++b) {
+        orc_tree_depths(parents + (size_t)b * sq, k, depth + (size_t)b * sq);
+        orc_tree_mask(parents + (size_t)b * sq, k, tmask + (size_t)b * sq * sq);
+    }
+
+    for (int m = 0; m < M; ++m)
+        orc_rmsnorm(x + (size_t)m * h, w->attn_norm, c->rms_eps, h, a + (size_t)m * h);
+    orc_linear(a, M, h, w->wq, qd, q);
+    orc_linear(a, M, h, w->wk, kd, kn);
+    orc_linear(a, M, h, w->wv, kd, vn);
+
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < sq; ++j) {
+            const int m = b * sq + j, pos = lens[b] + depth[m], row = lens[b] + j;
+            for (int hq = 0; hq < c->n_q_heads; ++hq)
+                orc_rope(q + (size_t)m * qd + (size_t)hq * d, d, pos, c->rope_base);
+            for (int hk = 0; hk < c->n_kv_heads; ++hk) {
+                orc_rope(kn + (size_t)m * kd + (size_t)hk * d, d, pos, c->rope_base);
+                for (int i = 0; i < d; ++i) {
+                    Kc[cache_off(c, b, hk, row) + i] = orc_f32_to_bf16(kn[(size_t)m * kd + hk * d + i]);
+                    Vc[cache_off(c, b, hk, row) + i] = orc_f32_to_bf16(vn[(size_t)m * kd + hk * d + i]);
+                }
+            }
+        }
+
+#pragma omp parallel for schedule(dynamic)
+    for (int mh = 0; mh < M * c->n_q_heads; ++mh) {
+        const int m = mh / c->n_q_heads, hq = mh % c->n_q_heads;
+        const int b = m / sq, j = m % sq, hk = hq / g;
+        const int n_rows = lens[b] + sq;
+        uint8_t *mask = malloc((size_t)n_rows);   /* row j of M: old cache visible, then the tree mask */
+        memset(mask, 1, (size_t)lens[b]);
+        memcpy(mask + lens[b], tmask + ((size_t)b * sq + j) * sq, (size_t)sq);
+        orc_attention_row_masked(q + (size_t)m * qd + (size_t)hq * d, Kc + cache_off(c, b, hk, 0),
+                                 Vc + cache_off(c, b, hk, 0), mask, n_rows, d,
+                                 ao + (size_t)m * qd + (size_t)hq * d);
+        free(mask);
+    }
+
+    orc_linear(ao, M, qd, w->wo, h, y);
+    for (size_t i = 0; i < (size_t)M * h; ++i)
+        x[i] += y[i];
+
+    for (int m = 0; m < M; ++m)
+        orc_rmsnorm(x + (size_t)m * h, w->mlp_norm, c->rms_eps, h, a + (size_t)m * h);
+    orc_linear(a, M, h, w->w_gate, c->ffn, gt);
+    orc_linear(a, M, h, w->w_up, c->ffn, up);
+    for (size_t i = 0; i < (size_t)M * c->ffn; ++i)
+        gt[i] = silu(gt[i]) * up[i];
+    orc_linear(gt, M, c->ffn, w->w_down, h, y);
+    for (size_t i = 0; i < (size_t)M * h; ++i)
+        x[i] += y[i];
+
+    free(a); free(q); free(kn); free(vn); free(ao); free(y); free(gt); free(up); free(depth); free(tmask);
+}
+
+/*
+ * Greedy acceptance on a draft tree for one sequence.  that[i] is the target's
+ * argmax after node i, i.e. its own choice for the token that follows node i.
+ * Starting at the root, step to the child whose token equals that[current]
+ * (children of a node carry distinct tokens in a trie; if not, the lowest node
+ * index wins) until no child matches.  path[0..n] are the nodes walked (path[0]
+ * = 0), n the number of accepted drafts, that[path[n]] the bonus token -- the
+ * emitted stream equals greedy decoding (Sec. 2).
+ */
+void orc_accept_tree(const int32_t *tokens, const int32_t *parent, const int32_t *that, int k,
+                     int32_t *accepted_len, int32_t *next_token, int32_t *path)
+{
+    int cur = 0, n = 0;
+    path[0] = 0;
+    for (;;) {
+        int next = -1;
+        for (int c2 = cur + 1; c2 <= k; ++c2)
+            if (parent[c2] == cur && tokens[c2] == that[cur]) { next = c2; break; }
+        if (next < 0) break;
+        cur = next;
+        path[++n] = cur;
+    }
+    *accepted_len = n;
+    *next_token = that[cur];
+}
+
+/* After acceptance the cache rows of the accepted nodes path[1..n] (at rows
+ * len + path[i]) move to rows len + i, so that the cache is again one
+ * contiguous row per position.  Kc/Vc: one layer, all sequences. */
+void orc_kv_compact(const orc_config *c, uint16_t *Kc, uint16_t *Vc, int b, int len,
+                    const int32_t *path, int n)
+{
+    for (int i = 1; i <= n; ++i) {
+        if (path[i] == i) continue;
+        for (int hk = 0; hk < c->n_kv_heads; ++hk) {
+            memcpy(Kc + cache_off(c, b, hk, len + i), Kc + cache_off(c, b, hk, len + path[i]),
+                   sizeof(uint16_t) * (size_t)c->head_dim);
+            memcpy(Vc + cache_off(c, b, hk, len + i), Vc + cache_off(c, b, hk, len + path[i]),
+                   sizeof(uint16_t) * (size_t)c->head_dim);
+        }
+    }
 }
