@@ -4,8 +4,9 @@
  * The paper (SSSD, arXiv 2411.05894) drafts candidate tokens on the host and
  * has the target model verify "the last generated token and the speculated
  * tokens" in a single forward pass (Sec. 2; Sec. 3.2, first paragraph).  This
- * library is that device-side step for a linear chain of k drafts per
- * sequence: one pass of a Llama-style decoder over b sequences x s_q = k+1
+ * library is that device-side step for k drafts per sequence, given as a
+ * linear chain (sssd_verify_step) or as a draft tree (sssd_verify_step_tree):
+ * one pass of a Llama-style decoder over b sequences x s_q = k+1
  * tokens (the operations of Table 2, App. B, with p = 1), K/V of all k+1 rows
  * appended in place to a per-sequence cache, then greedy acceptance.
  *
@@ -124,6 +125,44 @@ int sssd_verify_step(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
  */
 int sssd_kv_rollback(sssd_ctx *ctx, int32_t B, int32_t *lens, const int32_t *accepted_len,
                      const int32_t *new_lens, void *stream);
+
+/*
+ * One verification step over draft TREES, enqueued on `stream`.  The paper merges its
+ * candidates into a draft tree and verifies all nodes in one pass under an attention mask
+ * built from the tree (Sec. 3.1; the mask M of Table 2's attention row, App. B); a linear
+ * chain (sssd_verify_step) is the tree in which node i's parent is node i-1.
+ *   tokens        device int32 [B][k+1]; node 0 is the root = the last accepted token,
+ *                 nodes 1..k the drafts
+ *   parents       device int32 [B][k+1]; parents[b][i] in [0, i) for i >= 1 (entry 0 unused):
+ *                 nodes are numbered so that a parent precedes its children
+ *   accepted_len  device int32 [B] out; number of drafts on the accepted path, in 0..depth
+ *   next_token    device int32 [B] out; arg-max after the last accepted node (bonus token)
+ *   accepted_path device int32 [B][k+1] out; accepted_path[b][0] = 0, then the nodes
+ *                 walked: from the current node step to the child whose token equals the
+ *                 arg-max after the current node (the lowest node index if several children
+ *                 carry that token) until none does; entries past accepted_len[b] are -1.
+ *                 Accepted tokens + next_token is exactly what greedy decoding emits.
+ * Node i attends to the old cache, its ancestors and itself; its rotary position is
+ * lens[b] + depth(i); its K/V go to cache row lens[b] + i of every layer.  lens is not
+ * changed: sssd_kv_commit_tree moves the accepted rows into place and advances lens.
+ * Errors as for sssd_verify_step; a parent outside [0, i) is treated as i-1 and raises the
+ * same sticky flag.
+ */
+int sssd_verify_step_tree(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
+                          const int32_t *parents, const int32_t *lens, int32_t *accepted_len,
+                          int32_t *next_token, int32_t *accepted_path, void *stream);
+
+/*
+ * Commit a tree step, enqueued on `stream`: in every layer the K/V rows of the accepted nodes
+ * accepted_path[b][1..n] (n = accepted_len[b]) move from cache rows lens[b] + node to rows
+ * lens[b] + 1 .. lens[b] + n, so that the cache again holds one row per position; then
+ * lens[b] += n + 1 (device int32 [B], in-out).  accepted_len / accepted_path are the outputs
+ * of the tree step (device).  A path that is not strictly increasing within 1..k, or an
+ * n outside 0..k, leaves that sequence untouched and raises the sticky flag
+ * (sssd_verify_sync returns SSSD_ENOSPACE).
+ */
+int sssd_kv_commit_tree(sssd_ctx *ctx, int32_t B, int32_t k, int32_t *lens,
+                        const int32_t *accepted_len, const int32_t *accepted_path, void *stream);
 
 /* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call raised
  * the device flag (and clear it), else SSSD_OK. */

@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
                                        C.c_uint32, C.POINTER(vp)]
         l.sssd_verify_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
         l.sssd_kv_rollback.argtypes = [vp, i32, vp, vp, vp, vp]
+        l.sssd_verify_step_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        l.sssd_kv_commit_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
         l.sssd_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
@@ -149,6 +151,23 @@ class VerifyContext:
             assert t.dtype == torch.int32
         _check(lib().sssd_verify_step(self.handle, B, sq - 1, _ptr(tokens), _ptr(lens), _ptr(accepted_len),
                                       _ptr(next_token), _stream()), "sssd_verify_step")
+
+    def sssd_verify_step_tree(self, tokens: torch.Tensor, parents: torch.Tensor, lens: torch.Tensor,
+                              accepted_len: torch.Tensor, next_token: torch.Tensor, accepted_path: torch.Tensor) -> None:
+        B, sq = tokens.shape
+        assert parents.shape == tokens.shape and accepted_path.shape == tokens.shape
+        for t in (tokens, parents, lens, accepted_len, next_token, accepted_path):
+            assert t.dtype == torch.int32
+        _check(lib().sssd_verify_step_tree(self.handle, B, sq - 1, _ptr(tokens), _ptr(parents), _ptr(lens),
+                                           _ptr(accepted_len), _ptr(next_token), _ptr(accepted_path), _stream()),
+               "sssd_verify_step_tree")
+
+    def sssd_kv_commit_tree(self, lens: torch.Tensor, accepted_len: torch.Tensor, accepted_path: torch.Tensor) -> None:
+        B, sq = accepted_path.shape
+        for t in (lens, accepted_len, accepted_path):
+            assert t.dtype == torch.int32
+        _check(lib().sssd_kv_commit_tree(self.handle, B, sq - 1, _ptr(lens), _ptr(accepted_len), _ptr(accepted_path),
+                                         _stream()), "sssd_kv_commit_tree")
 
     def sssd_kv_rollback(self, lens: torch.Tensor, accepted_len: Optional[torch.Tensor] = None,
                          new_lens: Optional[torch.Tensor] = None) -> None:

@@ -22,7 +22,8 @@ struct Buffers {
     uint16_t *Qp, *Qp_lo;
     float *part_o, *part_ml, *part_val;
     int *part_idx;
-    int32_t *pos_base, *err_flag, *that_dbg;
+    int32_t *pos_base, *err_flag, *that_dbg, *rope_pos;
+    uint32_t *anc;
     float *rope_cs, *ssq1;
     uint8_t *staging;
     size_t staging_bytes;
@@ -128,6 +129,8 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.part_val = (float *)take((size_t)S.m_alloc * NTv * 4);
     b.part_idx = (int *)take((size_t)S.m_alloc * NTv * 4);
     b.pos_base = (int32_t *)take((size_t)D.max_batch * 4);
+    b.rope_pos = (int32_t *)take((size_t)S.m_alloc * 4);
+    b.anc = (uint32_t *)take((size_t)S.m_alloc * 4);
     b.err_flag = (int32_t *)take(4);
     b.ssq1 = (float *)take((size_t)S.m_alloc * (D.h / 16) * 4);
     b.that_dbg = (int32_t *)take((size_t)S.m_alloc * 4);
@@ -377,8 +380,13 @@ int sssd_debug_outputs(sssd_ctx *c, float *logits, float *hidden)
     return SSSD_OK;
 }
 
-int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int32_t *lens,
-                     int32_t *accepted_len, int32_t *next_token, void *stream)
+}  // extern "C"
+
+namespace {
+
+// The verify pass over chains (parents == nullptr) or draft trees.
+int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int32_t *parents, const int32_t *lens,
+             int32_t *accepted_len, int32_t *next_token, int32_t *path, void *stream)
 {
     if (!valid(c) || !tokens || !lens || !accepted_len || !next_token) return SSSD_EINVAL;
     const Dims &D = c->D;
@@ -387,19 +395,19 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
     hipStream_t s = (hipStream_t)stream;
     Buffers &W = c->W;
     const int M = B * (k + 1);
-    StepIO io{tokens, lens, accepted_len, next_token, B, k};
+    StepIO io{tokens, lens, accepted_len, next_token, B, k, parents, path};
 
     // Six launches per layer (QKV, attention, merge, O, gate/up, down) plus an epilogue launch
     // after every GEMM whose K is split over workgroups.
     {
         Prof p(c, s, SSSD_PROF_ELEM);
         HIP_TRY(launch_fused_embed(D, io, c->embed, c->layers[0].attn_norm, W.X, W.Ah_hi, W.Ah_lo, W.ssq1, W.pos_base,
-                                   W.err_flag, s));
+                                   W.rope_pos, W.anc, W.err_flag, s));
     }
     FusedGemmArgs f{};
     f.M = M; f.h = D.h; f.d = D.d; f.nq = D.nq; f.nkv = D.nkv; f.seq_pad = D.seq_pad; f.k = k;
     f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps;
-    f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
+    f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.rope_pos = W.rope_pos; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
     f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
     const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
     f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
@@ -423,7 +431,7 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         f.n_units = (D.nq + 2 * D.nkv) * (D.d / 32); f.Ntot = D.qd + 2 * D.kd;
         HIP_TRY(fgemm(FEPI_QKV));
         {
-            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
+            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
             Prof p(c, s, SSSD_PROF_ATTN);
             HIP_TRY(launch_attention(D, a, s));
         }
@@ -457,6 +465,35 @@ int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, c
         Prof p(c, s, SSSD_PROF_ACCEPT);
         HIP_TRY(launch_accept(D, io, W.part_val, W.part_idx, D.V / 16, W.that_dbg, s));
     }
+    return SSSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sssd_verify_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int32_t *lens,
+                     int32_t *accepted_len, int32_t *next_token, void *stream)
+{
+    return run_step(c, B, k, tokens, nullptr, lens, accepted_len, next_token, nullptr, stream);
+}
+
+int sssd_verify_step_tree(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int32_t *parents,
+                          const int32_t *lens, int32_t *accepted_len, int32_t *next_token, int32_t *accepted_path,
+                          void *stream)
+{
+    if (!parents || !accepted_path) return SSSD_EINVAL;
+    return run_step(c, B, k, tokens, parents, lens, accepted_len, next_token, accepted_path, stream);
+}
+
+int sssd_kv_commit_tree(sssd_ctx *c, int32_t B, int32_t k, int32_t *lens, const int32_t *accepted_len,
+                        const int32_t *accepted_path, void *stream)
+{
+    if (!valid(c) || !lens || !accepted_len || !accepted_path) return SSSD_EINVAL;
+    if (B <= 0 || k < 0) return SSSD_EINVAL;
+    if (B > c->D.max_batch || k > c->D.max_k) return SSSD_ECAPACITY;
+    HIP_TRY(launch_kv_compact(c->D, c->Kc, c->Vc, c->S.kv_layer_elems, B, k, lens, accepted_len, accepted_path,
+                              c->W.err_flag, (hipStream_t)stream));
     return SSSD_OK;
 }
 
@@ -593,10 +630,10 @@ int sssd_op_attention(sssd_ctx *c, int32_t layer, int32_t B, int32_t k, const fl
     if (B > D.max_batch || k > D.max_k) return SSSD_ECAPACITY;
     hipStream_t s = (hipStream_t)stream;
     Buffers &W = c->W;
-    HIP_TRY(launch_lens(D, B, k, lens, W.pos_base, W.err_flag, s));
+    HIP_TRY(launch_lens(D, B, k, lens, W.pos_base, W.rope_pos, W.anc, W.err_flag, s));
     HIP_TRY(launch_q_pack(D, q, B, k, W.Qp, W.Qp_lo, s));
     uint16_t *Kl = c->Kc + (size_t)layer * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)layer * c->S.kv_layer_elems;
-    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
+    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
     HIP_TRY(launch_attention(D, a, s));
     HIP_TRY(launch_unpack_act(W.Aq_hi, W.Aq_lo, B * (k + 1), D.qd, out, s));
     return SSSD_OK;

@@ -2,9 +2,10 @@
 //
 // Table 2 (App. B), attention row: A_out = softmax(Q K^T / sqrt(d) + M) V with
 // K, V of shape (b, n_kv, s_kv + s_q, d).  Its FLOPs:IO ratio is ~ g*s_q, so the
-// operation is bound by streaming the cache; the mask M of a linear draft chain
-// is "row j sees positions 0 .. lens[b]+j" and is applied arithmetically (no mask
-// tensor is read).
+// operation is bound by streaming the cache.  The mask M is never read as a tensor:
+// every query row sees the old cache (rows below lens[b]) and, of the k+1 new rows, the
+// ones named by a 32-bit word per query node -- itself and its ancestors in the draft
+// tree (Sec. 3.1); for a linear chain that is "row j sees new rows 0..j".
 //
 // One workgroup owns one (sequence, kv head, position chunk).  All g*(k+1) query rows
 // that share the kv head are processed against the chunk, one 16-row tile per wave,
@@ -98,9 +99,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = NEG_BIG, l_run = 0.f;
-    int j = (rt * 16 + c) / D.g;   // query row -> draft index
+    int j = (rt * 16 + c) / D.g;   // query row -> node of the chain or tree
     if (j > a.k) j = a.k;
-    const int limit = len + j;     // last visible position
+    const uint32_t vis = a.anc[b * (a.k + 1) + j];   // visible new rows: bit i = cache row len + i
     const float scale = 1.4426950408889634f * rsqrtf((float)HD);  // log2(e)/sqrt(d)
 
     stage_store(0);
@@ -129,9 +130,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int t = t0 + 16 * u + 4 * q + r;
+                const int rel = t0 + 16 * u + 4 * q + r - len;   // < 0: old cache, always visible
                 float x = s[u][r] * scale;
-                if (t > limit) x = NEG_BIG;
+                if (rel >= 0 && (rel > 31 || !((vis >> rel) & 1u))) x = NEG_BIG;
                 v[u * 4 + r] = x;
                 mx = fmaxf(mx, x);
             }

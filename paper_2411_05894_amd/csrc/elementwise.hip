@@ -49,6 +49,72 @@ __global__ void accept_kernel(StepIO io, const int32_t *that)
     io.next_token[b] = that[b * sq + n];
 }
 
+// Greedy acceptance on draft trees (the candidate tree the paper verifies, Sec. 3.1): from the
+// root, step to the child whose token is the arg-max after the current node (the lowest node index
+// if several children carry it) until none does.  One thread per sequence.
+__global__ void accept_tree_kernel(StepIO io, const int32_t *that)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= io.B) return;
+    const int sq = io.k + 1;
+    const int32_t *tok = io.tokens + b * sq, *par = io.parents + b * sq, *th = that + b * sq;
+    int32_t *path = io.path + b * sq;
+    int cur = 0, n = 0;
+    path[0] = 0;
+    for (;;) {
+        int next = -1;
+        for (int c = cur + 1; c <= io.k; ++c)
+            if (par[c] == cur && tok[c] == th[cur]) { next = c; break; }
+        if (next < 0) break;
+        cur = next;
+        path[++n] = cur;
+    }
+    for (int i = n + 1; i <= io.k; ++i) path[i] = -1;
+    io.accepted_len[b] = n;
+    io.next_token[b] = th[cur];
+}
+
+// grid = (nkv, B, L), block = d threads.  Thread i moves channel i of the accepted rows, one row
+// after the other in path order: destinations lens + 1 .. lens + n never run ahead of the sources
+// still to be read (path[i] >= i, increasing), and each thread touches its own channel only.
+__global__ void kv_compact_kernel(Dims D, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int k, const int32_t *lens,
+                                  const int32_t *accepted_len, const int32_t *path)
+{
+    const int kvh = blockIdx.x, b = blockIdx.y, l = blockIdx.z, i = threadIdx.x;
+    const int len = lens[b], n = accepted_len[b];
+    if (len < 0 || n < 0 || n > k || len + k + 1 > D.max_seq) return;   // flagged by kv_commit_kernel
+    const size_t slab = (size_t)l * kv_layer_elems + ((size_t)b * D.nkv + kvh) * D.seq_pad * D.d;
+    uint16_t *kc = Kc + slab, *vc = Vc + slab;
+    int prev = 0;
+    for (int s = 1; s <= n; ++s) {
+        const int node = path[b * (k + 1) + s];
+        if (node <= prev || node > k) return;        // not an increasing path: leave the rest alone (flagged)
+        prev = node;
+        if (node == s) continue;
+        kc[(size_t)(len + s) * D.d + i] = kc[(size_t)(len + node) * D.d + i];
+        vc[vcache_index(len + s, i, D.d)] = vc[vcache_index(len + node, i, D.d)];
+    }
+}
+
+// After kv_compact_kernel: lens[b] += accepted_len[b] + 1; malformed input raises the error flag
+// and leaves lens[b] alone.
+__global__ void kv_commit_kernel(Dims D, int B, int k, int32_t *lens, const int32_t *accepted_len, const int32_t *path,
+                                 int32_t *err_flag)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int len = lens[b], n = accepted_len[b];
+    bool ok = len >= 0 && n >= 0 && n <= k && len + k + 1 <= D.max_seq;
+    int prev = 0;
+    for (int s = 1; ok && s <= n; ++s) {
+        const int node = path[b * (k + 1) + s];
+        ok = node > prev && node <= k;
+        prev = node;
+    }
+    if (ok) lens[b] = len + n + 1;
+    else *err_flag = 1;
+}
+
 __global__ void rollback_kernel(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -111,7 +177,9 @@ __global__ void q_pack_kernel(Dims D, const float *q, int k, uint16_t *Qp, uint1
     Qp_lo[idx] = lo;
 }
 
-__global__ void lens_kernel(Dims D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag)
+// Validated lens and the row geometry of linear chains (kernel-level attention entry point).
+__global__ void lens_kernel(Dims D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *rope_pos, uint32_t *anc,
+                            int32_t *err_flag)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
@@ -121,6 +189,10 @@ __global__ void lens_kernel(Dims D, int B, int k, const int32_t *lens, int32_t *
         len = 0;
     }
     pos_base[b] = len;
+    for (int j = 0; j <= k; ++j) {
+        rope_pos[b * (k + 1) + j] = len + j;
+        anc[b * (k + 1) + j] = 0xFFFFFFFFu >> (31 - j);
+    }
 }
 
 // Reorder a row-major bf16 matrix [N][K] into operand tiles (one 16-byte lane record per thread).
@@ -146,10 +218,12 @@ __global__ void pack_weight_kernel(const uint16_t *src, u32x4 *dst, int N, int K
 }
 
 
-// grid = M rows, 512 threads.  Validates lens/tokens; x = E[token]; packed x*gamma; sums of squares.
+// grid = M rows, 512 threads.  Validates lens/tokens/parents; row geometry (depth and visible new
+// rows of the node, from the draft tree or the chain); x = E[token]; packed x*gamma; sums of squares.
 __global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, const uint16_t *embed, const uint16_t *gamma,
                                                           float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq,
-                                                          int32_t *pos_base, int32_t *err_flag)
+                                                          int32_t *pos_base, int32_t *rope_pos, uint32_t *anc,
+                                                          int32_t *err_flag)
 {
     const int m = blockIdx.x, b = m / (io.k + 1), j = m % (io.k + 1);
     int tok = io.tokens[m];
@@ -157,13 +231,32 @@ __global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, con
         if (threadIdx.x == 0) *err_flag = 1;
         tok = 0;
     }
-    if (j == 0 && threadIdx.x == 0) {
+    if (threadIdx.x == 0) {
         int len = io.lens[b];
         if (len < 0 || len + io.k + 1 > D.max_seq) {
             *err_flag = 1;
             len = 0;
         }
-        pos_base[b] = len;
+        if (j == 0) pos_base[b] = len;
+        int depth = j;
+        uint32_t vis = 0xFFFFFFFFu >> (31 - j);
+        if (io.parents) {
+            // walk to the root; a parent outside [0, node) is treated as node-1 and flagged
+            depth = 0;
+            vis = 1u << j;
+            for (int i = j; i > 0;) {
+                int p = io.parents[b * (io.k + 1) + i];
+                if (p < 0 || p >= i) {
+                    *err_flag = 1;
+                    p = i - 1;
+                }
+                i = p;
+                vis |= 1u << i;
+                ++depth;
+            }
+        }
+        rope_pos[m] = len + depth;
+        anc[m] = vis;
     }
     const uint16_t *row = embed + (size_t)tok * D.h;
     const int KT = (D.h + 31) >> 5, NSS = D.h >> 4;
@@ -191,13 +284,25 @@ hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val,
     hipLaunchKernelGGL(row_argmax_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, part_val, part_idx, NT, that);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(accept_kernel, dim3((io.B + 63) / 64), dim3(64), 0, s, io, that);
+    if (io.parents) hipLaunchKernelGGL(accept_tree_kernel, dim3((io.B + 63) / 64), dim3(64), 0, s, io, that);
+    else hipLaunchKernelGGL(accept_kernel, dim3((io.B + 63) / 64), dim3(64), 0, s, io, that);
     return hipGetLastError();
 }
 
 hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens, hipStream_t s)
 {
     hipLaunchKernelGGL(rollback_kernel, dim3((B + 63) / 64), dim3(64), 0, s, B, lens, accepted_len, new_lens);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_compact(const Dims &D, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int B, int k, int32_t *lens,
+                             const int32_t *accepted_len, const int32_t *path, int32_t *err_flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(kv_compact_kernel, dim3(D.nkv, B, D.L), dim3(D.d), 0, s, D, Kc, Vc, kv_layer_elems, k, lens, accepted_len,
+                       path);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kv_commit_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, accepted_len, path, err_flag);
     return hipGetLastError();
 }
 
@@ -229,10 +334,10 @@ hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *
     return hipGetLastError();
 }
 
-hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag,
-                       hipStream_t s)
+hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *rope_pos, uint32_t *anc,
+                       int32_t *err_flag, hipStream_t s)
 {
-    hipLaunchKernelGGL(lens_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, pos_base, err_flag);
+    hipLaunchKernelGGL(lens_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, pos_base, rope_pos, anc, err_flag);
     return hipGetLastError();
 }
 
@@ -247,10 +352,10 @@ hipError_t launch_pack_weight(const uint16_t *src, uint16_t *dst, int N, int K, 
 }
 
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
-                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,
-                              hipStream_t s)
+                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos, uint32_t *anc,
+                              int32_t *err_flag, hipStream_t s)
 {
     hipLaunchKernelGGL(fused_embed_kernel, dim3(io.B * (io.k + 1)), dim3(512), 0, s, D, io, embed, gamma, X, A_hi, A_lo, ssq,
-                       pos_base, err_flag);
+                       pos_base, rope_pos, anc, err_flag);
     return hipGetLastError();
 }

@@ -10,7 +10,15 @@ struct StepIO {
     const int32_t *tokens, *lens;
     int32_t *accepted_len, *next_token;
     int B, k;
+    const int32_t *parents;   // draft trees [B][k+1] (node 0 = root, parents[b][i] < i), or nullptr: linear chains
+    int32_t *path;            // tree steps: accepted root-to-node path [B][k+1] out (entries past accepted_len = -1)
 };
+
+// Per-row geometry of a step, written by the embedding kernel and read by the QKV epilogue and
+// the attention kernel: node j of sequence b is row m = b*(k+1)+j; its K/V go to cache row
+// pos_base[b] + j, its rotary position is rope_pos[m] = pos_base[b] + depth(j), and it attends to
+// the old cache plus the new rows whose bit is set in anc[m] (itself and its ancestors).  A
+// linear chain is the tree with parent(j) = j-1: depth j, bits 0..j.
 
 // ------------------------------------------------------------ fused GEMMs ----
 enum FusedEpilogue {
@@ -33,7 +41,8 @@ struct FusedGemmArgs {
     uint16_t *out_hi, *out_lo;    // RESID (K = h) / SWIGLU (KT_out k-tiles): packed operands of the next GEMM
     int KT_out;
     const float *rope_cs;         // QKV
-    const int32_t *pos_base;
+    const int32_t *pos_base;      // QKV: cache row of (b, j) is pos_base[b] + j
+    const int32_t *rope_pos;      // QKV: rotary position of row m
     uint16_t *Qp, *Qp_lo, *Kc, *Vc;  // Kc, Vc: this layer's cache
     float *logits, *part_val;     // LM
     int *part_idx;
@@ -59,14 +68,20 @@ hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, boo
                               hipEvent_t t1);
 hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
-                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *err_flag,
-                              hipStream_t s);
+                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos,
+                              uint32_t *anc, int32_t *err_flag, hipStream_t s);
 
-// Merge per-tile arg-max partials, then greedy prefix acceptance.
+// Merge per-tile arg-max partials, then greedy acceptance (longest matching prefix of a chain, or
+// the walk from the root of a draft tree when io.parents is set).
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
                          int32_t *that_dbg, hipStream_t s);
 hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens,
                            hipStream_t s);
+// Tree commit: in every layer move the K/V rows of the accepted nodes path[b][1..n] from cache rows
+// lens[b] + path[b][i] to lens[b] + i, then lens[b] += n + 1.  Kc/Vc: whole cache (all layers).
+hipError_t launch_kv_compact(const Dims &D, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int B, int k,
+                             int32_t *lens, const int32_t *accepted_len, const int32_t *path, int32_t *err_flag,
+                             hipStream_t s);
 hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, int t0, int n_rows,
                           uint16_t *k_ext, uint16_t *v_ext, bool import, hipStream_t s);
 
@@ -74,8 +89,8 @@ hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, i
 hipError_t launch_pack_act(const float *X, int M, int K, uint16_t *A_hi, uint16_t *A_lo, hipStream_t s);
 hipError_t launch_unpack_act(const uint16_t *A_hi, const uint16_t *A_lo, int M, int K, float *X, hipStream_t s);
 hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, uint16_t *Qp_lo, hipStream_t s);
-hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *err_flag,
-                       hipStream_t s);
+hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *rope_pos,
+                       uint32_t *anc, int32_t *err_flag, hipStream_t s);
 
 // ------------------------------------------------------------ attention ----
 struct AttnArgs {
@@ -83,6 +98,7 @@ struct AttnArgs {
     const uint16_t *Qp_lo;     // bf16 lo part: q ~= hi + lo
     const uint16_t *Kc, *Vc;   // this layer's cache
     const int32_t *pos_base;   // validated lens
+    const uint32_t *anc;       // [B*(k+1)] visible new rows of each query row (bit i = row pos_base + i)
     float *part_o;             // [b][kv head][n_splits][q_rows_pad][d]
     float *part_ml;            // [b][kv head][n_splits][q_rows_pad][2]  (running max in log2 units, sum)
     uint16_t *out_hi, *out_lo; // packed activations for the O projection (K = nq*d)

@@ -104,11 +104,11 @@ __device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m
         v0 *= rs;
         v1 *= rs;
         const int b = m / (a.k + 1), j = m % (a.k + 1);
-        const int pos = a.pos_base[b] + j;
+        const int pos = a.pos_base[b] + j;              // cache row of node j
         const int half = a.d >> 1, ch = pair * 16 + c;  // channel of v0; v1 is ch + half
         const size_t slab = (size_t)b * a.nkv * a.seq_pad * a.d;
         if (head < a.nq + a.nkv) {
-            const float2 cs = *reinterpret_cast<const float2 *>(a.rope_cs + ((size_t)pos * half + ch) * 2);
+            const float2 cs = *reinterpret_cast<const float2 *>(a.rope_cs + ((size_t)a.rope_pos[m] * half + ch) * 2);
             const float y0 = v0 * cs.x - v1 * cs.y, y1 = v0 * cs.y + v1 * cs.x;
             if (head < a.nq) {
                 const int g = a.nq / a.nkv, kvh = head / g, hl = head % g, rr = j * g + hl;
@@ -431,12 +431,12 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int blocks_pe
                 int head = cb / bph;
                 const int ch = col - head * a.d;              // first-half channel of v0[0]
                 const int b = m / (a.k + 1), j = m % (a.k + 1);
-                const int pos = a.pos_base[b] + j;
+                const int pos = a.pos_base[b] + j;            // cache row of node j
                 const size_t slab = (size_t)b * a.nkv * a.seq_pad * a.d;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { v0.v[e] *= rs; v1.v[e] *= rs; }
                 if (head < a.nq + a.nkv) {
-                    const float *cs = a.rope_cs + ((size_t)pos * half + ch) * 2;
+                    const float *cs = a.rope_cs + ((size_t)a.rope_pos[m] * half + ch) * 2;
                     const Vec8 cs0 = load8(cs), cs1 = load8(cs + 8);   // (cos, sin) of channels ch..ch+3, ch+4..ch+7
                     Vec8 y0, y1;
 #pragma unroll

@@ -74,6 +74,69 @@ class Pair:
                 "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
 
 
+def step_tree(pair: "Pair", tokens: torch.Tensor, parents: torch.Tensor, lens: torch.Tensor):
+    """Run the library's tree step on CPU int32 tensors tokens/parents [B,k+1], lens [B]."""
+    B, sq = tokens.shape
+    dev = pair.dev
+    t = tokens.to(dev, torch.int32).contiguous()
+    par = parents.to(dev, torch.int32).contiguous()
+    ln = lens.to(dev, torch.int32).contiguous()
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty(B, sq, dtype=torch.int32, device=dev)
+    pair.ctx.sssd_verify_step_tree(t, par, ln, acc, nxt, path)
+    rc = pair.ctx.sssd_verify_sync()
+    assert rc == 0, sv.strerror(rc)
+    M = B * sq
+    return {"logits": pair.logits[:M].cpu().view(B, sq, -1), "hidden": pair.hidden[:M].cpu().view(B, sq, -1),
+            "accepted_len": acc.cpu(), "next_token": nxt.cpu(), "path": path.cpu(),
+            "dev": {"accepted_len": acc, "path": path}}
+
+
+def walk_tree(tokens: Sequence[int], parents: Sequence[int], that: Sequence[int]) -> List[int]:
+    """The accepted path the interface defines, from a given arg-max vector (plain Python)."""
+    cur, path = 0, [0]
+    while True:
+        nxt = [c for c in range(cur + 1, len(tokens)) if parents[c] == cur and tokens[c] == that[cur]]
+        if not nxt:
+            return path
+        cur = nxt[0]
+        path.append(cur)
+
+
+def compare_tree_step(gpu: Dict[str, torch.Tensor], ref: Dict[str, torch.Tensor], tokens: torch.Tensor,
+                      parents: torch.Tensor, tol: float = LOGIT_TOL):
+    """Logits element by element; arg-max ids where the oracle's margin decides them; the accepted
+    path against the oracle's when every row on it is decided, and always against the library's
+    own logits.  Returns (max_err, exempt_rows, rows)."""
+    B, sq = tokens.shape
+    max_err, exempt = 0.0, 0
+    for b in range(B):
+        rl, gl = ref["logits"][b], gpu["logits"][b]
+        err = (rl - gl).abs().max().item()
+        max_err = max(max_err, err)
+        assert err <= tol, f"sequence {b}: max abs logit error {err}"
+        decided = []
+        for j in range(sq):
+            t1, t2 = oracle.top2(rl[j])
+            decided.append((t1 - t2) > MARGIN)
+            if decided[-1]:
+                assert int(gl[j].argmax()) == int(ref["that"][b, j]), f"argmax differs at ({b},{j})"
+            else:
+                exempt += 1
+        ref_path = ref["path"][b]
+        n = int(gpu["accepted_len"][b])
+        g_path = gpu["path"][b].tolist()
+        if all(decided[i] for i in ref_path):
+            assert g_path[: n + 1] == ref_path, f"accepted path differs for sequence {b}"
+            assert int(gpu["next_token"][b]) == int(ref["next_token"][b])
+        own = walk_tree(tokens[b].tolist(), parents[b].tolist(), gl.argmax(-1).tolist())
+        assert g_path[: n + 1] == own and n == len(own) - 1
+        assert all(x == -1 for x in g_path[n + 1:])
+        assert int(gpu["next_token"][b]) == int(gl[own[-1]].argmax())
+    return max_err, exempt, B * sq
+
+
 def compare_step(gpu: Dict[str, torch.Tensor], ref: Dict[str, torch.Tensor], tokens: torch.Tensor,
                  seqs: Optional[Sequence[int]] = None, tol: float = LOGIT_TOL):
     """Element-by-element logits check plus the id rule; ``seqs`` maps oracle
