@@ -18,7 +18,7 @@ from sssd_synth import (MODEL_SHAPES, TensorId, global_weight_specs, layer_weigh
                         make_weight, uniform_int)
 
 sys.path.insert(0, os.path.dirname(__file__))
-from harness import LOGIT_TOL, Pair, compare_step  # noqa: E402
+from harness import LOGIT_TOL, Pair, compare_step, compare_tree_step, step_tree  # noqa: E402
 
 DEV = "cuda:0"
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -65,6 +65,31 @@ def test_cfg2_8b_b1_ctx2048_k_sweep(pair_8b):
         gpu = p.step(tk, lens)
         err, ex, rows = compare_step(gpu, sub, tk)
         progress(f"cfg2 k={k}: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+
+
+@pytest.mark.timeout(300)
+def test_cfg2_shape_draft_tree_k16(pair_8b):
+    """The 8B shape at B=1, context 2048, with the 16 drafts arranged as a seeded random TREE
+    (Sec. 3.1: the candidates are verified as a tree under its attention mask) instead of a chain."""
+    p, s = pair_8b, pair_8b.shape
+    k = 16
+    p.prefill_random_kv(4, 0, 2048, oracle_slot=0)
+    tokens = uniform_int(4, TensorId.TOKENS, (1, k + 1), 0, s.vocab - 1)
+    raw = uniform_int(4, TensorId.LENS, (k + 1,), 0, 1 << 20).tolist()
+    parents = torch.tensor([[0] + [raw[i] % i for i in range(1, k + 1)]], dtype=torch.int32)
+    lens = torch.tensor([2048], dtype=torch.int32)
+    t = time.time()
+    ref = p.oracle.verify_step_tree(tokens, parents, lens, compact=False)
+    # plant the oracle's own choice after the root in one child of the root: that child's row is unchanged
+    # (its token was not an input of the root row), but the walk now accepts at least one draft
+    kid = max(c for c in range(1, k + 1) if int(parents[0, c]) == 0)
+    tokens[0, kid] = int(ref["that"][0, 0])
+    ref = p.oracle.verify_step_tree(tokens, parents, lens, compact=False)
+    progress(f"cfg2-tree: two oracle passes took {time.time() - t:.1f}s, tree {parents[0].tolist()}")
+    gpu = step_tree(p, tokens, parents, lens)
+    err, ex, rows = compare_tree_step(gpu, ref, tokens, parents)
+    progress(f"cfg2-tree k={k}: max logit err {err:.2e}, exempt rows {ex}/{rows}, accepted {int(ref['accepted_len'][0])}")
+    assert int(ref["accepted_len"][0]) >= 1
 
 
 @pytest.mark.timeout(300)
