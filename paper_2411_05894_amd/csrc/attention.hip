@@ -64,29 +64,38 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
     const u32x4 *Qs = reinterpret_cast<const u32x4 *>(a.Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD) + (size_t)rt * KS * 64 + lane;
     const u32x4 *Ql = reinterpret_cast<const u32x4 *>(a.Qp_lo + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD) + (size_t)rt * KS * 64 + lane;
 
-    // staging: record i of a block; K rows are contiguous in the cache, so is a whole V block
-    u32x4 kst[SPT], vst[SPT];
-    auto stage_load = [&](int t0) {
+    // staging: record i of a block; K rows are contiguous in the cache, so is a whole V block.
+    // Two register stages: while block i is processed out of LDS, block i+1 sits in one stage
+    // (loaded during the previous iteration, moved to LDS at the end of this one) and block i+2 is
+    // being fetched into the other, so two blocks (32 KiB with d = 128) are in flight per workgroup.
+    // Every load is issued unconditionally -- past the chunk's end it re-reads the last block, which
+    // is never stored -- because a load under a branch would make every later wait a full drain.
+    struct Stage {
+        u32x4 k[SPT], v[SPT];
+    };
+    const int t_last = t_begin + ((t_end - t_begin - 1) & ~31);   // first position of the chunk's last block
+    auto stage_load = [&](Stage &st, int t0) {
+        if (t0 > t_last) t0 = t_last;
+#pragma unroll
+        for (int i = 0; i < SPT; ++i) {
+            int rec = threadIdx.x + i * T;
+            if (NREC % T != 0 && rec >= NREC) rec = NREC - 1;
+            st.k[i] = __builtin_nontemporal_load(Kc + (size_t)t0 * CPR + rec);
+            st.v[i] = __builtin_nontemporal_load(Vc + (size_t)(t0 >> 5) * NREC + rec);
+        }
+    };
+    auto stage_store = [&](int buf, const Stage &st) {
 #pragma unroll
         for (int i = 0; i < SPT; ++i) {
             const int rec = threadIdx.x + i * T;
             if (NREC % T == 0 || rec < NREC) {
-                kst[i] = Kc[(size_t)t0 * CPR + rec];
-                vst[i] = Vc[(size_t)(t0 >> 5) * NREC + rec];
+                Ks[buf][(rec / CPR) * KROW + rec % CPR] = st.k[i];
+                Vs[buf][rec] = st.v[i];
             }
         }
     };
-    auto stage_store = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < SPT; ++i) {
-            const int rec = threadIdx.x + i * T;
-            if (NREC % T == 0 || rec < NREC) {
-                Ks[buf][(rec / CPR) * KROW + rec % CPR] = kst[i];
-                Vs[buf][rec] = vst[i];
-            }
-        }
-    };
-    stage_load(t_begin);
+    Stage sa, sb;
+    stage_load(sa, t_begin);
 
     // q ~= hi + lo (two bf16), so the scores carry fp32-level accuracy although K is bf16.
     u32x4 qreg[KS], qlo[KS];
@@ -104,14 +113,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
     const uint32_t vis = a.anc[b * (a.k + 1) + j];   // visible new rows: bit i = cache row len + i
     const float scale = 1.4426950408889634f * rsqrtf((float)HD);  // log2(e)/sqrt(d)
 
-    stage_store(0);
+    stage_store(0, sa);
+    stage_load(sa, t_begin + 32);
     __syncthreads();
 
-    int buf = 0;
-    for (int t0 = t_begin; t0 < t_end; t0 += 32, buf ^= 1) {
-        const bool more = t0 + 32 < t_end;
-        if (more) stage_load(t0 + 32);
-
+    // one block of 32 positions out of LDS buffer `buf`
+    auto block = [&](int buf, int t0) {
         f32x4 s[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -125,47 +132,65 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
         }
         // s[u][r] is the score of position t0 + 16u + 4q + r for query row rt*16 + c.
         float v[8];
-        float mx = NEG_BIG;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int rel = t0 + 16 * u + 4 * q + r - len;   // < 0: old cache, always visible
-                float x = s[u][r] * scale;
-                if (rel >= 0 && (rel > 31 || !((vis >> rel) & 1u))) x = NEG_BIG;
-                v[u * 4 + r] = x;
-                mx = fmaxf(mx, x);
-            }
+            for (int r = 0; r < 4; ++r) v[u * 4 + r] = s[u][r] * scale;
+        if (t0 + 32 > len) {   // the block holds new rows: apply the node's visibility word
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int rel = t0 + 16 * u + 4 * q + r - len;   // < 0: old cache, always visible
+                    if (rel >= 0 && (rel > 31 || !((vis >> rel) & 1u))) v[u * 4 + r] = NEG_BIG;
+                }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = exp2f(m_run - m_new);
-        m_run = m_new;
+        // The exponent's reference m_run follows the running maximum lazily: it moves (and the
+        // accumulators are rescaled) only when some row's maximum has outgrown it by more than 2^8,
+        // so most blocks skip the rescale.  Any reference gives the same softmax; probabilities stay
+        // below 2^8 and the partial (o, l, m_run) handed to the merge is consistent with it.
+        if (__any(mx > m_run + 8.f)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+        }
         float psum = 0.f;
         uint32_t pk[4], pkl[4];
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            const float p0 = exp2f(v[e] - m_new), p1 = exp2f(v[e + 1] - m_new);
-            uint16_t h0, l0, h1, l1;   // p ~= hi + lo: the probabilities keep ~16 mantissa bits
-            split_bf16(p0, h0, l0);
-            split_bf16(p1, h1, l1);
+            const float p0 = __builtin_amdgcn_exp2f(v[e] - m_run), p1 = __builtin_amdgcn_exp2f(v[e + 1] - m_run);
+            split_bf16x2(p0, p1, pk[e >> 1], pkl[e >> 1]);   // p ~= hi + lo: the probabilities keep ~16 mantissa bits
             psum += p0 + p1;
-            pk[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            pkl[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
-        l_run = l_run * alpha + psum;
+        l_run += psum;
         const u32x4 pb = u32x4{pk[0], pk[1], pk[2], pk[3]}, pl = u32x4{pkl[0], pkl[1], pkl[2], pkl[3]};
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const u32x4 vv = Vs[buf][dt * 64 + lane];
-            o[dt] *= alpha;
             o[dt] = mfma(vv, pb, o[dt]);
             o[dt] = mfma(vv, pl, o[dt]);
         }
+    };
 
-        // Buffer buf^1 was read in the previous iteration, which every wave left through the
-        // barrier below before anyone got here.
-        if (more) stage_store(buf ^ 1);
+    // Entering an iteration at t0: LDS buffer 0 holds block t0, stage sa block t0+32.  The LDS buffer
+    // written at the end of a half-iteration was read in the previous one, which every wave left
+    // through a barrier before anyone got here.
+    for (int t0 = t_begin; t0 < t_end; t0 += 64) {
+        stage_load(sb, t0 + 64);
+        block(0, t0);
+        if (t0 + 32 >= t_end) break;
+        stage_store(1, sa);
+        __syncthreads();
+        stage_load(sa, t0 + 96);
+        block(1, t0 + 32);
+        if (t0 + 64 >= t_end) break;
+        stage_store(0, sb);
         __syncthreads();
     }
 

@@ -26,6 +26,21 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
     lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
 
+// Two values at once through the hardware conversion (v_cvt_pk_bf16_f32, round to nearest even):
+// the bf16 pair (x0 low half, x1 high half), and the hi + lo split of both.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float x0, float x1)
+{
+    const f32x2_t v = {x0, x1};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ void split_bf16x2(float x0, float x1, uint32_t &hi, uint32_t &lo)
+{
+    hi = pack_bf16x2(x0, x1);
+    lo = pack_bf16x2(x0 - bits_f32(hi << 16), x1 - bits_f32(hi & 0xFFFF0000u));
+}
+
 // ---- MFMA operand tile order -------------------------------------------------
 // v_mfma_f32_16x16x32_bf16 reads, per lane l, 8 bf16 of a 16 x 32 operand tile:
 // row/column l % 16, k-slots 8*(l/16) .. 8*(l/16)+7.  A "packed" matrix stores
