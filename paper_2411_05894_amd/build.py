@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsssd_verify.so")
 DRIVER = os.path.join(HERE, "step_driver")
-SOURCES = ["api.hip", "attention.hip", "elementwise.hip", "stream_gemm.hip"]
+SOURCES = ["api.hip", "attention.hip", "elementwise.hip", "stream_gemm.hip", "drafter.cpp"]
 import shlex
 FLAGS = shlex.split(os.environ.get("SSSD_EXTRA_HIPCC_FLAGS", "")) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          # packed-fp32 VALU forms are kept off on the test machines
@@ -17,9 +17,13 @@ FLAGS = shlex.split(os.environ.get("SSSD_EXTRA_HIPCC_FLAGS", "")) + ["--offload-
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+    obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
     os.makedirs(os.path.dirname(obj), exist_ok=True)
-    subprocess.run(["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+    if src.endswith(".cpp"):   # host-only code (the drafter)
+        subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-c", os.path.join(CSRC, src), "-o", obj],
+                       check=True)
+    else:
+        subprocess.run(["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
     return obj
 
 

@@ -22,6 +22,7 @@ from .gen import (  # noqa: F401
     normal_bf16,
     uniform_int,
     uniform_bf16,
+    repetitive_stream,
     ModelShape,
     MODEL_SHAPES,
     layer_weight_specs,

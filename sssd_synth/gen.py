@@ -103,6 +103,28 @@ def uniform_bf16(seed: int, tensor_id: int, shape, low: float, high: float, devi
     return (u * (high - low) + low).to(torch.float32).to(torch.bfloat16).view(*shape)
 
 
+def repetitive_stream(seed: int, tensor_id: int, n: int, vocab: int, n_templates: int = 12, min_len: int = 4,
+                      max_len: int = 14, noise: float = 0.05) -> "list[int]":
+    """Token stream with the n-gram repetition that retrieval-based drafting feeds on: a seeded
+    set of templates (random token runs of min_len..max_len tokens) concatenated in a seeded random
+    order, with a fraction `noise` of the tokens replaced by uniform-random ids.  It stands in for
+    the prompt / self-output and datastore text of the paper's chat, code and maths workloads."""
+    lens = uniform_int(seed, tensor_id * 8 + 1, (n_templates,), min_len, max_len).tolist()
+    body = uniform_int(seed, tensor_id * 8 + 2, (n_templates, max_len), 0, vocab - 1).tolist()
+    templates = [body[i][: lens[i]] for i in range(n_templates)]
+    pick = uniform_int(seed, tensor_id * 8 + 3, (n,), 0, n_templates - 1).tolist()
+    flip = uniform_int(seed, tensor_id * 8 + 4, (n,), 0, 999_999).tolist()
+    rand = uniform_int(seed, tensor_id * 8 + 5, (n,), 0, vocab - 1).tolist()
+    out: "list[int]" = []
+    i = 0
+    while len(out) < n:
+        out += templates[pick[i]]
+        i += 1
+    out = out[:n]
+    thresh = int(noise * 1_000_000)
+    return [rand[j] if flip[j] < thresh else out[j] for j in range(n)]
+
+
 class TensorId:
     """Tensor ids: globals below 16, per-layer tensors at 16 + 16*layer + slot."""
     EMBED, LM_HEAD, FINAL_NORM, TOKENS, LENS, PROMPT, REPLACE_POS, REPLACE_TOK = range(8)
