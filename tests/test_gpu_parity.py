@@ -60,6 +60,8 @@ def test_gemm_vs_oracle(N, K):
 @pytest.mark.parametrize("shape_name,B,k,ctxs", [
     ("tiny", 2, 4, [0, 37]), ("tiny", 1, 0, [130]), ("tiny", 3, 7, [31, 32, 95]),
     ("8b", 2, 8, [2048, 1000]), ("8b", 1, 16, [300]),
+    ("8b", 1, 31, [70]),          # the largest k: 128 query rows per kv head = 8 row tiles, two passes over the cache
+    ("70b", 1, 5, [33]),          # g = 8
 ])
 def test_attention_vs_oracle(shape_name, B, k, ctxs):
     s = MODEL_SHAPES[shape_name]

@@ -64,6 +64,32 @@ def test_tree_step_random_trees_vs_oracle():
     assert ex < r // 2
 
 
+def test_largest_tree_and_degenerate_trees():
+    """k = 31 (32 nodes: every bit of the visibility word), a star (all drafts children of the root),
+    an empty context, and k = 0 (the root alone)."""
+    s = MODEL_SHAPES["tiny"]
+    B, k = 3, 31
+    p = Pair(s, seed=23, max_batch=B, max_k=k, max_seq=128)
+    ctxs = [0, 1, 64]
+    for b in range(B):
+        p.prefill_random_kv(28, b, ctxs[b], oracle_slot=b)
+    lens = torch.tensor(ctxs, dtype=torch.int32)
+    parents = torch.tensor([seeded_tree(29, 0, k), [0] * (k + 1), [0] + list(range(k))], dtype=torch.int32)
+    tokens = uniform_int(30, 1, (B, k + 1), 0, s.vocab - 1)
+    tokens = plant_greedy_path(p, tokens, parents, lens, depth=3)
+    ref = p.oracle.verify_step_tree(tokens, parents, lens, compact=False)
+    gpu = step_tree(p, tokens, parents, lens)
+    e, ex, r = compare_tree_step(gpu, ref, tokens, parents)
+    say(f"k=31 trees: worst logit err {e:.2e}, exempt rows {ex}/{r}, accepted {ref['accepted_len'].tolist()}")
+    # k = 0: the tree is the root
+    t0 = tokens[:, :1].contiguous()
+    p0 = parents[:, :1].contiguous()
+    ref0 = p.oracle.verify_step_tree(t0, p0, lens, compact=False)
+    gpu0 = step_tree(p, t0, p0, lens)
+    compare_tree_step(gpu0, ref0, t0, p0)
+    assert gpu0["accepted_len"].tolist() == [0, 0, 0] and gpu0["path"].tolist() == [[0], [0], [0]]
+
+
 def test_chain_given_as_tree_is_the_chain_step():
     """parent(i) = i-1: the same kernels on the same geometry, so logits are bit-identical."""
     s = MODEL_SHAPES["tiny"]
