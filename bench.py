@@ -23,7 +23,7 @@ PEAK_HBM_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each
 # calibrated against a 1 GiB copy kernel); source: profiles/verify_step_8b_b1_ctx2048_k8_hbm_traffic.md.
 # Only the workload those runs covered has a figure.
-MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "pgemm_kernel"): 120.44e6}
+MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "pgemm_kernel"): 120.88e6}
 
 WORKLOADS = {
     # name: (shape, B, ctx spec, k, k sweep)
@@ -81,7 +81,8 @@ def main() -> int:
                for n, slot, shp in layer_weight_specs(shape)} for l in range(shape.n_layers)]
     g = {n: make_weight(seed, n, tid, shp, device=dev) for n, tid, shp in global_weight_specs(shape)}
     host_sample = None
-    n_cpu_layers = min(shape.n_layers, 4)
+    # oracle sample sized for 10-30 s of host work: every layer of the 8B shape, 8 layers of the 70B shape
+    n_cpu_layers = min(shape.n_layers, 32 if shape.hidden <= 4096 else 8)
     if not args.no_cpu_baseline:
         host_sample = ([{n: t.cpu() for n, t in layers[l].items()} for l in range(n_cpu_layers)],
                        {n: t.cpu() for n, t in g.items()})
@@ -131,6 +132,15 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # Part of set-up: a second of steps so that the clocks have settled before the W warm-up steps
+    # (the first launches after the idle set-up phase measured 3-5 % slower than steady state).
+    settle = tokens_for(k)
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < 1.0:
+        for _ in range(10):
+            ctx.sssd_verify_step(settle, lens, acc, nxt)
+        torch.cuda.synchronize()
+
     # ---- the timed region ----
     ms = time_steps(k, args.warmup, args.steps)
     assert ctx.sssd_verify_sync() == 0
@@ -157,6 +167,32 @@ def main() -> int:
                 "bytes_per_launch": round(bytes_per_launch), "launches_per_step": launches,
                 "avg_launch_us": round(ms_per_launch * 1e3, 2)}
     classes_ms = {n: round(v["ms"] / prof_steps, 4) for n, v in prof.items()}
+
+    # ---- the same step over draft trees (seeded random trees of k+1 nodes) and the host drafter's cost ----
+    tree_ms = None
+    if k >= 1:
+        raw = uniform_int(4, TensorId.LENS + 7, (B, k + 1), 0, 1 << 20).tolist()
+        par = torch.tensor([[0] + [raw[b][i] % i for i in range(1, k + 1)] for b in range(B)], dtype=torch.int32, device=dev)
+        path = torch.zeros(B, k + 1, dtype=torch.int32, device=dev)
+        for _ in range(3):
+            ctx.sssd_verify_step_tree(tok, par, lens, acc, nxt, path)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        n_tree = max(3, args.sweep_steps)
+        for _ in range(n_tree):
+            ctx.sssd_verify_step_tree(tok, par, lens, acc, nxt, path)
+        torch.cuda.synchronize()
+        tree_ms = (time.perf_counter() - t) * 1e3 / n_tree
+    from paper_2411_05894_amd import drafter as dr
+    from sssd_synth import repetitive_stream
+    d = dr.Drafter(n_sequences=1)
+    d.sssd_draft_datastore_add(repetitive_stream(9, 1, 200_000, vocab=shape.vocab, n_templates=64))
+    d.sssd_draft_input_append(0, repetitive_stream(9, 2, 1024, vocab=shape.vocab, n_templates=64))
+    t = time.perf_counter()
+    n_prop = 200
+    for _ in range(n_prop):
+        d.sssd_draft_propose(0, k + 1)
+    draft_us = (time.perf_counter() - t) * 1e6 / n_prop
 
     # ---- latency curve over k ----
     curve = {}
@@ -201,6 +237,8 @@ def main() -> int:
         "latency_ms_vs_k": {str(kk): round(v, 4) for kk, v in curve.items()},
         "latency_ratio_vs_k0": ratio,
         "kernel_class_ms_per_step": classes_ms,
+        "tree_step_ms": None if tree_ms is None else round(tree_ms, 4),
+        "host_draft_us_per_proposal": round(draft_us, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
         "setup_s": round(setup_s, 1),
