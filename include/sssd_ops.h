@@ -39,6 +39,11 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
 int sssd_op_attention(sssd_ctx *ctx, int32_t layer, int32_t B, int32_t k, const float *q, const int32_t *lens,
                       float *out, void *stream);
 
+/* The row sampler of sssd_verify_step_tree_sampled on its own: logits device fp32 [rows][vocab],
+ * uniforms device fp32 [rows], sampled device int32 [rows] out; `sampling` is host memory. */
+int sssd_op_sample(const float *logits, int32_t rows, int32_t vocab, const sssd_sampling_params *sampling,
+                   const float *uniforms, int32_t *sampled, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

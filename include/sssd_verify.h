@@ -153,6 +153,40 @@ int sssd_verify_step_tree(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *to
                           int32_t *next_token, int32_t *accepted_path, void *stream);
 
 /*
+ * The tree step with SAMPLING instead of greedy acceptance, enqueued on `stream`.  The paper runs
+ * SSSD beyond greedy decoding with a simplified speculative sampling that preserves the target
+ * distribution without draft probabilities (Sec. 4.4: temperature 0.6, top-p 0.95; Fig. 5:
+ * temperature 0.7, top-p 0.8, top-k 20).  An n-gram draft is a point mass, for which the
+ * accept/resample rule of speculative sampling equals: draw ONE token t from the target
+ * distribution of the current node; step to the child that carries t if there is one (the lowest
+ * node index among equal tokens), else emit t and stop.  Per row the distribution is
+ *   order O : logit descending, token id ascending among equal logits
+ *   S_k     : the first top_k tokens of O (all if top_k == 0 or top_k >= vocab)
+ *   w_i     : exp((logit_i - max logit) / temperature)
+ *   S       : the shortest prefix of O, at least one token, whose w-sum reaches top_p * sum(w over S_k)
+ *   sample  : r = u * sum(w over S); the first token of S in ascending token id whose running
+ *             w-sum exceeds r.
+ *   sampling       host; temperature > 0, top_k >= 0, 0 < top_p <= 1
+ *   uniforms       device float [B][k+1]; u in [0, 1) for node i of sequence b (the caller's
+ *                  random numbers: the library draws none)
+ *   logits_scratch device float, at least B*(k+1)*vocab elements (the step's logits; also the
+ *                  row order of sssd_debug_outputs)
+ *   accepted_len / next_token / accepted_path as in sssd_verify_step_tree, with the sampled
+ *   token in place of the arg-max.  Everything else (cache rows, positions, lens, errors) is
+ *   identical to sssd_verify_step_tree; sssd_kv_commit_tree commits the step.
+ */
+typedef struct {
+    float temperature;
+    int32_t top_k; /* 0 = off */
+    float top_p;   /* 1 = off */
+} sssd_sampling_params;
+int sssd_verify_step_tree_sampled(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
+                                  const int32_t *parents, const int32_t *lens,
+                                  const sssd_sampling_params *sampling, const float *uniforms,
+                                  float *logits_scratch, int32_t *accepted_len, int32_t *next_token,
+                                  int32_t *accepted_path, void *stream);
+
+/*
  * Commit a tree step, enqueued on `stream`: in every layer the K/V rows of the accepted nodes
  * accepted_path[b][1..n] (n = accepted_len[b]) move from cache rows lens[b] + node to rows
  * lens[b] + 1 .. lens[b] + n, so that the cache again holds one row per position; then

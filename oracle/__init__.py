@@ -156,6 +156,83 @@ def accept_tree(tokens: Sequence[int], parents: Sequence[int], that: Sequence[in
     return acc.value, nxt.value, path[: acc.value + 1].tolist()
 
 
+def sample_row(logits_row: torch.Tensor, temperature: float, top_k: int, top_p: float, u: float,
+               w_noise: float = 0.0, logit_noise: float = 0.0):
+    """One token from the target distribution of a row, in fp64, as the definition reads (the
+    simplified speculative sampling of Sec. 4.4 needs nothing else from the target):
+    order O by (logit descending, token id ascending); S_k = first top_k of O (all if 0 or >= V);
+    w = exp((z - max z) / T); S = shortest prefix of O whose w-sum reaches top_p * sum(w over S_k);
+    the sample is the first token of S, in ascending token id, whose running w-sum exceeds u * sum(w over S).
+
+    Returns (token, margin).  margin says how robust the decision is against an implementation whose
+    weights carry a relative error up to ``w_noise`` and whose logits differ by up to ``logit_noise``:
+    the relative distance of u * Z_S to the nearest step of the inverse CDF, minus the relative mass
+    of the tokens whose membership of S such noise could change (tokens at the nucleus cut, and
+    tokens whose logit is within logit_noise of the top-k threshold); 0 if the drawn token itself is
+    one of those.  The parity tests exempt rows whose margin is below the noise."""
+    z = logits_row.detach().cpu().double().numpy()
+    V = z.shape[0]
+    ids = np.arange(V)
+    order = np.lexsort((ids, -z))
+    K = V if top_k == 0 or top_k >= V else int(top_k)
+    Sk = order[:K]
+    w = np.exp((z - z.max()) / float(temperature))
+    Zk = w[Sk].sum()
+    uncertain = np.zeros(V, dtype=bool)
+    if K < V and logit_noise > 0.0:
+        zk = z[order[K - 1]]
+        uncertain |= np.abs(z - zk) <= logit_noise
+        uncertain |= np.abs(z - z[order[K]]) <= logit_noise
+    if top_p < 1.0:
+        c = np.cumsum(w[Sk])
+        target = float(top_p) * Zk
+        n = int(np.searchsorted(c, target, side="left"))       # first index with c >= target
+        n = min(n, K - 1)
+        S = Sk[: n + 1]
+        if w_noise > 0.0:
+            d = 2.0 * w_noise * Zk
+            lo = min(int(np.searchsorted(c, target - d, side="left")), K - 1)
+            hi = min(int(np.searchsorted(c, target + d, side="left")), K - 1)
+            uncertain[Sk[lo + 1: hi + 1]] = True
+            if lo < n:
+                uncertain[Sk[lo + 1: n + 1]] = True
+    else:
+        S = Sk
+    S = np.sort(S)
+    c = np.cumsum(w[S])
+    ZS = c[-1]
+    r = float(u) * ZS
+    idx = int(np.searchsorted(c, r, side="right"))             # first index with c > r
+    idx = min(idx, len(S) - 1)
+    margin = abs(c[idx] - r) / ZS
+    if idx > 0:
+        margin = min(margin, abs(c[idx - 1] - r) / ZS)
+    token = int(S[idx])
+    if uncertain[token]:
+        margin = 0.0
+    else:
+        margin -= w[uncertain].sum() / ZS
+    return token, float(max(margin, 0.0))
+
+
+def target_distribution(logits_row: torch.Tensor, temperature: float, top_k: int, top_p: float) -> np.ndarray:
+    """Probability of every token under sample_row's rule (zero outside S), fp64."""
+    z = logits_row.detach().cpu().double().numpy()
+    V = z.shape[0]
+    order = np.lexsort((np.arange(V), -z))
+    K = V if top_k == 0 or top_k >= V else int(top_k)
+    Sk = order[:K]
+    w = np.exp((z - z.max()) / float(temperature))
+    S = Sk
+    if top_p < 1.0:
+        c = np.cumsum(w[Sk])
+        n = min(int(np.searchsorted(c, float(top_p) * c[-1], side="left")), K - 1)
+        S = Sk[: n + 1]
+    p = np.zeros(V)
+    p[S] = w[S] / w[S].sum()
+    return p
+
+
 def counters_reset():
     lib().orc_counters_reset()
 
@@ -270,6 +347,42 @@ class OracleModel:
                 for l in range(self.shape.n_layers):
                     lib().orc_kv_compact(C.byref(self.cfg), _p(self.K[l]), _p(self.V[l]), b, int(ln[b]), _p(pa), a)
         return {"logits": logits, "that": that, "accepted_len": acc, "next_token": nxt, "path": paths}
+
+    def verify_step_tree_sampled(self, tokens: torch.Tensor, parents: torch.Tensor, lens: torch.Tensor,
+                                 temperature: float, top_k: int, top_p: float, uniforms: torch.Tensor,
+                                 compact: bool = True):
+        """The tree pass with target-only speculative sampling (Sec. 4.4): node i of sequence b draws
+        one token from its target distribution with uniforms[b][i]; the walk follows the child that
+        carries the drawn token.  Returns logits, ``sampled`` [B][k+1], ``margin`` [B][k+1],
+        ``accepted_len``, ``next_token``, ``path``."""
+        B, sq = tokens.shape
+        k = sq - 1
+        par = parents.to(torch.int32).contiguous()
+        ln = lens.to(torch.int32).contiguous()
+        x = self.embed(tokens)
+        for l in range(self.shape.n_layers):
+            lw = self._lw(l)
+            lib().orc_layer_verify_tree(C.byref(self.cfg), C.byref(lw), _p(x), _p(self.K[l]), _p(self.V[l]),
+                                        _p(ln), _p(par), B, k)
+        logits = self.lm_head(x).view(B, sq, -1)
+        sampled = torch.empty(B, sq, dtype=torch.int32)
+        margin = torch.empty(B, sq, dtype=torch.float64)
+        acc = torch.empty(B, dtype=torch.int32)
+        nxt = torch.empty(B, dtype=torch.int32)
+        paths = []
+        for b in range(B):
+            for j in range(sq):
+                t, mg = sample_row(logits[b, j], temperature, top_k, top_p, float(uniforms[b, j]))
+                sampled[b, j], margin[b, j] = t, mg
+            a, n, path = accept_tree(tokens[b].tolist(), par[b].tolist(), sampled[b].tolist())
+            acc[b], nxt[b] = a, n
+            paths.append(path)
+            if compact:
+                pa = np.ascontiguousarray(path + [0] * (sq - len(path)), dtype=np.int32)
+                for l in range(self.shape.n_layers):
+                    lib().orc_kv_compact(C.byref(self.cfg), _p(self.K[l]), _p(self.V[l]), b, int(ln[b]), _p(pa), a)
+        return {"logits": logits, "sampled": sampled, "margin": margin, "accepted_len": acc, "next_token": nxt,
+                "path": paths}
 
     def decode_token(self, b: int, token: int, pos: int) -> torch.Tensor:
         """Plain autoregressive step of sequence ``b``: logits [V] for the token at ``pos``."""

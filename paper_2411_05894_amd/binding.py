@@ -32,6 +32,10 @@ class ModelConfig(C.Structure):
                [(n, C.c_int32) for n in ("max_batch", "max_k", "max_seq")]
 
 
+class SamplingParams(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("top_k", C.c_int32), ("top_p", C.c_float)]
+
+
 _PER_LAYER = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "mlp_norm")
 
 
@@ -61,6 +65,8 @@ def lib() -> C.CDLL:
         l.sssd_kv_rollback.argtypes = [vp, i32, vp, vp, vp, vp]
         l.sssd_verify_step_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         l.sssd_kv_commit_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        l.sssd_verify_step_tree_sampled.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(SamplingParams), vp, vp, vp, vp, vp, vp]
+        l.sssd_op_sample.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
         l.sssd_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
@@ -162,6 +168,21 @@ class VerifyContext:
                                            _ptr(accepted_len), _ptr(next_token), _ptr(accepted_path), _stream()),
                "sssd_verify_step_tree")
 
+    def sssd_verify_step_tree_sampled(self, tokens: torch.Tensor, parents: torch.Tensor, lens: torch.Tensor,
+                                      sampling: SamplingParams, uniforms: torch.Tensor, logits_scratch: torch.Tensor,
+                                      accepted_len: torch.Tensor, next_token: torch.Tensor,
+                                      accepted_path: torch.Tensor) -> None:
+        B, sq = tokens.shape
+        assert parents.shape == tokens.shape and accepted_path.shape == tokens.shape and uniforms.shape == tokens.shape
+        assert uniforms.dtype == torch.float32 and logits_scratch.dtype == torch.float32
+        assert logits_scratch.numel() >= B * sq * self.cfg.vocab
+        for t in (tokens, parents, lens, accepted_len, next_token, accepted_path):
+            assert t.dtype == torch.int32
+        _check(lib().sssd_verify_step_tree_sampled(self.handle, B, sq - 1, _ptr(tokens), _ptr(parents), _ptr(lens),
+                                                   C.byref(sampling), _ptr(uniforms), _ptr(logits_scratch),
+                                                   _ptr(accepted_len), _ptr(next_token), _ptr(accepted_path), _stream()),
+               "sssd_verify_step_tree_sampled")
+
     def sssd_kv_commit_tree(self, lens: torch.Tensor, accepted_len: torch.Tensor, accepted_path: torch.Tensor) -> None:
         B, sq = accepted_path.shape
         for t in (lens, accepted_len, accepted_path):
@@ -243,4 +264,13 @@ def sssd_op_gemm(a_hi: torch.Tensor, a_lo: torch.Tensor, w_packed: torch.Tensor,
     scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=a_hi.device)
     _check(lib().sssd_op_gemm(_ptr(a_hi), _ptr(a_lo), _ptr(w_packed), M, N, K, _ptr(out), _ptr(scratch), nbytes,
                               _stream()), "sssd_op_gemm")
+    return out
+
+
+def sssd_op_sample(logits: torch.Tensor, sampling: SamplingParams, uniforms: torch.Tensor) -> torch.Tensor:
+    rows, vocab = logits.shape
+    assert logits.dtype == torch.float32 and uniforms.dtype == torch.float32 and uniforms.numel() == rows
+    out = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    _check(lib().sssd_op_sample(_ptr(logits), rows, vocab, C.byref(sampling), _ptr(uniforms), _ptr(out), _stream()),
+           "sssd_op_sample")
     return out

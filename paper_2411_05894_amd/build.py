@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsssd_verify.so")
 DRIVER = os.path.join(HERE, "step_driver")
-SOURCES = ["api.hip", "attention.hip", "elementwise.hip", "stream_gemm.hip", "drafter.cpp"]
+SOURCES = ["api.hip", "attention.hip", "elementwise.hip", "stream_gemm.hip", "sampling.hip", "drafter.cpp"]
 import shlex
 FLAGS = shlex.split(os.environ.get("SSSD_EXTRA_HIPCC_FLAGS", "")) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          # packed-fp32 VALU forms are kept off on the test machines

@@ -385,8 +385,15 @@ int sssd_debug_outputs(sssd_ctx *c, float *logits, float *hidden)
 namespace {
 
 // The verify pass over chains (parents == nullptr) or draft trees.
+struct Sampling {
+    float temperature, top_p;
+    int32_t top_k;
+    const float *uniforms;   // device [B][k+1]
+    float *logits;           // device scratch [B*(k+1)][vocab]
+};
+
 int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int32_t *parents, const int32_t *lens,
-             int32_t *accepted_len, int32_t *next_token, int32_t *path, void *stream)
+             int32_t *accepted_len, int32_t *next_token, int32_t *path, void *stream, const Sampling *smp = nullptr)
 {
     if (!valid(c) || !tokens || !lens || !accepted_len || !next_token) return SSSD_EINVAL;
     const Dims &D = c->D;
@@ -408,7 +415,7 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
     f.M = M; f.h = D.h; f.d = D.d; f.nq = D.nq; f.nkv = D.nkv; f.seq_pad = D.seq_pad; f.k = k;
     f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps;
     f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.rope_pos = W.rope_pos; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
-    f.logits = c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
+    f.logits = smp ? smp->logits : c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
     const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
     f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
     auto fgemm = [&](int epi) -> hipError_t {
@@ -461,7 +468,13 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
     f.W0 = (const u32x4 *)c->lm_head; f.NT = D.V / 16;
     f.n_units = f.NT; f.Ntot = D.V;
     HIP_TRY(fgemm(FEPI_LM));
-    {
+    if (smp) {
+        if (c->dbg_logits)
+            HIP_TRY(hipMemcpyAsync(c->dbg_logits, smp->logits, (size_t)M * D.V * 4, hipMemcpyDeviceToDevice, s));
+        Prof p(c, s, SSSD_PROF_ACCEPT);
+        HIP_TRY(launch_sample_rows(smp->logits, M, D.V, smp->temperature, smp->top_k, smp->top_p, smp->uniforms, W.that_dbg, s));
+        HIP_TRY(launch_accept(D, io, nullptr, nullptr, D.V / 16, W.that_dbg, s));
+    } else {
         Prof p(c, s, SSSD_PROF_ACCEPT);
         HIP_TRY(launch_accept(D, io, W.part_val, W.part_idx, D.V / 16, W.that_dbg, s));
     }
@@ -484,6 +497,18 @@ int sssd_verify_step_tree(sssd_ctx *c, int32_t B, int32_t k, const int32_t *toke
 {
     if (!parents || !accepted_path) return SSSD_EINVAL;
     return run_step(c, B, k, tokens, parents, lens, accepted_len, next_token, accepted_path, stream);
+}
+
+int sssd_verify_step_tree_sampled(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int32_t *parents,
+                                  const int32_t *lens, const sssd_sampling_params *sampling, const float *uniforms,
+                                  float *logits_scratch, int32_t *accepted_len, int32_t *next_token,
+                                  int32_t *accepted_path, void *stream)
+{
+    if (!parents || !accepted_path || !sampling || !uniforms || !logits_scratch) return SSSD_EINVAL;
+    if (!(sampling->temperature > 0.f) || sampling->top_k < 0 || !(sampling->top_p > 0.f) || sampling->top_p > 1.f)
+        return SSSD_EINVAL;
+    Sampling smp{sampling->temperature, sampling->top_p, sampling->top_k, uniforms, logits_scratch};
+    return run_step(c, B, k, tokens, parents, lens, accepted_len, next_token, accepted_path, stream, &smp);
 }
 
 int sssd_kv_commit_tree(sssd_ctx *c, int32_t B, int32_t k, int32_t *lens, const int32_t *accepted_len,
@@ -618,6 +643,17 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
     bool more = false;
     HIP_TRY(launch_stream_gemm(a, FEPI_STORE, (hipStream_t)stream, &more, nullptr, nullptr));
     if (more) HIP_TRY(launch_stream_epilogue(a, FEPI_STORE, (hipStream_t)stream));
+    return SSSD_OK;
+}
+
+int sssd_op_sample(const float *logits, int32_t rows, int32_t vocab, const sssd_sampling_params *sampling,
+                   const float *uniforms, int32_t *sampled, void *stream)
+{
+    if (!logits || !sampling || !uniforms || !sampled || rows <= 0 || vocab <= 0) return SSSD_EINVAL;
+    if (!(sampling->temperature > 0.f) || sampling->top_k < 0 || !(sampling->top_p > 0.f) || sampling->top_p > 1.f)
+        return SSSD_EINVAL;
+    HIP_TRY(launch_sample_rows(logits, rows, vocab, sampling->temperature, sampling->top_k, sampling->top_p, uniforms, sampled,
+                               (hipStream_t)stream));
     return SSSD_OK;
 }
 

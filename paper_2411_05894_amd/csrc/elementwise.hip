@@ -281,9 +281,11 @@ hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val,
                          int32_t *that, hipStream_t s)
 {
     (void)D;
-    hipLaunchKernelGGL(row_argmax_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, part_val, part_idx, NT, that);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (part_val) {
+        hipLaunchKernelGGL(row_argmax_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, part_val, part_idx, NT, that);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (io.parents) hipLaunchKernelGGL(accept_tree_kernel, dim3((io.B + 63) / 64), dim3(64), 0, s, io, that);
     else hipLaunchKernelGGL(accept_kernel, dim3((io.B + 63) / 64), dim3(64), 0, s, io, that);
     return hipGetLastError();

@@ -73,8 +73,13 @@ hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *e
 
 // Merge per-tile arg-max partials, then greedy acceptance (longest matching prefix of a chain, or
 // the walk from the root of a draft tree when io.parents is set).
+// With part_val == nullptr `that` already holds the target's choice per row (sampled tokens) and only the walk runs.
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
-                         int32_t *that_dbg, hipStream_t s);
+                         int32_t *that, hipStream_t s);
+// One token per row drawn from softmax(logits / temperature) restricted by top_k (0: off) and top_p
+// (1: off), with the caller's uniform number per row; sampling.hip states the exact definition.
+hipError_t launch_sample_rows(const float *logits, int rows, int V, float temperature, int top_k, float top_p,
+                              const float *uniforms, int32_t *sampled, hipStream_t s);
 hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens,
                            hipStream_t s);
 // Tree commit: in every layer move the K/V rows of the accepted nodes path[b][1..n] from cache rows
