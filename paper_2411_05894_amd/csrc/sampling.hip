@@ -20,7 +20,7 @@
 //
 // One workgroup of 1024 threads per row.  Both selections are radix selects over the 32-bit logit
 // pattern (four 8-bit digits, most significant first): top-k on counts, top-p on masses.  Masses
-// are 32.32 fixed-point integers accumulated with integer LDS atomics, so every sum is exact and
+// are 1.31 fixed-point integers accumulated in 64 bits with integer LDS atomics, so every sum is exact and
 // independent of the order of accumulation: the kernel is deterministic, and a tie at a threshold
 // is resolved by token id exactly as the definition says.  The row stays in L2 across the passes.
 #include "kernels.h"
@@ -28,6 +28,7 @@
 namespace {
 
 constexpr int ST = 1024;   // threads per row
+constexpr int MAX_BATCH = 64;   // batches of 512 ids per wave: vocabularies up to 16 * 64 * 512 tokens
 
 // Order-preserving map of a finite float to uint32: larger float -> larger key.
 __device__ __forceinline__ uint32_t order_key(float z)
@@ -42,26 +43,122 @@ struct RowCtx {
     float mx, scale;   // w = exp2((z - mx) * scale)
 };
 
+// Weight of a token as a 1.31 fixed-point integer: w * 2^31 is exact in fp32 (a power-of-two scale)
+// and fits 32 bits because w <= 1.
 __device__ __forceinline__ uint64_t fix_mass(const RowCtx &r, float z)
 {
-    const float w = __builtin_amdgcn_exp2f((z - r.mx) * r.scale);   // in (0, 1]
-    return (uint64_t)((double)w * 4294967296.0);
+    const float w = __builtin_amdgcn_exp2f((z - r.mx) * r.scale);   // in [0, 1]
+    return (uint64_t)(uint32_t)(w * 2147483648.0f);
 }
 
-// Scan 256 bins from the top: the first bin g with above + (mass of higher bins) + bin[g] >= target.
-// Returns g and adds the mass of the higher bins to `above`.  One thread.
-template <typename T> __device__ int pick_bin(const T *bins, T target, T &above)
+// Wave 0 scans 256 bins from the top: the bin g with above + (sum of higher bins) < target <= that + bins[g]
+// (bin 0 if the target is never reached).  Every lane returns g and the sum of the bins above g;
+// lane l owns bins 4l .. 4l+3.
+template <typename T> __device__ int pick_bin(const T *bins, T target, T above, T &higher, int lane)
 {
-    T acc = 0;
-    for (int g = 255; g >= 0; --g) {
-        if (above + acc + bins[g] >= target) {
-            above += acc;
-            return g;
-        }
-        acc += bins[g];
+    T v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = bins[4 * lane + e];
+    const T mine = v[0] + v[1] + v[2] + v[3];
+    T suffix = mine;   // sum over lanes >= lane
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const T o = __shfl_down(suffix, off);
+        if (lane + off < 64) suffix += o;
     }
-    above += acc - bins[0];
-    return 0;
+    T hi = suffix - mine;   // sum of the bins of higher lanes
+    int g = -1;
+    T hg = 0;
+#pragma unroll
+    for (int e = 3; e >= 0; --e) {
+        if (g < 0 && above + hi + v[e] >= target) { g = 4 * lane + e; hg = hi; }
+        hi += v[e];
+    }
+    // the highest bin that qualifies wins
+    const unsigned long long found = __ballot(g >= 0);
+    const int src = found ? 63 - __clzll(found) : 0;
+    int gs = __shfl(g, src);
+    T hs = __shfl(hg, src);
+    if (!found) { gs = 0; hs = __shfl(suffix, 0) - __shfl(v[0], 0); }
+    higher = hs;
+    return gs;
+}
+
+// Histogram accumulation through a private run per thread: consecutive elements that fall into the
+// same bin (the leading digits of a row's logits mostly do) are summed in registers and reach LDS as
+// one atomic add when the bin changes, so a hot bin is not hit by an atomic per element.
+struct BinRun {
+    uint32_t bin, count;
+    uint64_t mass;
+    bool open;
+};
+__device__ __forceinline__ void run_flush(BinRun &r, uint32_t *chist, uint64_t *mhist)
+{
+    if (!r.open) return;
+    if (chist) atomicAdd(&chist[r.bin], r.count);
+    if (mhist) atomicAdd((unsigned long long *)&mhist[r.bin], (unsigned long long)r.mass);
+    r.open = false;
+}
+__device__ __forceinline__ void run_add(BinRun &r, uint32_t bin, uint64_t mass, uint32_t *chist, uint64_t *mhist)
+{
+    if (r.open && r.bin == bin) {
+        r.count += 1;
+        r.mass += mass;
+        return;
+    }
+    run_flush(r, chist, mhist);
+    r.bin = bin;
+    r.count = 1;
+    r.mass = mass;
+    r.open = true;
+}
+
+// body(i, z, valid) for i = begin + first, begin + first + stride, ... below end, in ascending order.
+// The loads go out eight at a time: a pass is bound by load latency, not by bandwidth (the row is in L2).
+// Every thread makes the same number of calls (valid = false past the end), so body may use wave-wide
+// operations.
+constexpr int SU = 8;
+template <typename F>
+__device__ __forceinline__ void for_row(const float *z, int begin, int end, int first, int stride, F body)
+{
+    for (int base = begin; base < end; base += stride * SU) {
+        float zz[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int i = base + u * stride + first;
+            zz[u] = i < end ? z[i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int i = base + u * stride + first;
+            body(i, zz[u], i < end);
+        }
+    }
+}
+
+// The whole row, any order: 16-byte loads (four tokens per thread and load) when the row allows it.
+template <typename F> __device__ __forceinline__ void for_whole_row(const float *z, int V, bool vec4, int tid, F body)
+{
+    if (!vec4) {
+        for_row(z, 0, V, tid, ST, body);
+        return;
+    }
+    const f32x4 *z4 = reinterpret_cast<const f32x4 *>(z);
+    const int V4 = V >> 2;
+    for (int base = 0; base < V4; base += ST * SU) {
+        f32x4 zz[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int i = base + u * ST + tid;
+            zz[u] = i < V4 ? z4[i] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int i = base + u * ST + tid;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) body(4 * i + e, zz[u][e], i < V4);
+        }
+    }
 }
 
 // grid = rows, block = 1024.
@@ -71,11 +168,11 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
     __shared__ uint32_t chist[256];
     __shared__ uint64_t mhist[256];
     __shared__ float red_f[16];
-    __shared__ uint64_t red_u[16];
     __shared__ uint32_t red_c[16];
     __shared__ uint32_t sh_prefix, sh_need, sh_count_b;
-    __shared__ uint64_t sh_above, sh_total;
-    __shared__ int sh_wave, sh_token;
+    __shared__ uint64_t sh_above, sh_total, sh_target;
+    __shared__ int sh_wave, sh_batch, sh_token;
+    __shared__ uint64_t sub[16][MAX_BATCH];   // mass of S per (wave, batch of 512 ids)
 
     const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     RowCtx r;
@@ -84,7 +181,8 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
 
     // ---- max ----
     float mx = -INFINITY;
-    for (int i = tid; i < V; i += ST) mx = fmaxf(mx, r.z[i]);
+    const bool vec4 = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(r.z) & 15) == 0;
+    for_whole_row(r.z, V, vec4, tid, [&](int, float z, bool ok) { if (ok) mx = fmaxf(mx, z); });
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if (lane == 0) red_f[wave] = mx;
@@ -96,23 +194,28 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
     __syncthreads();
 
     // ---- top-k: key_a = key of the top_k-th token of O, n_a = how many tokens with exactly that key are kept ----
-    uint32_t key_a = 0, n_a = 0;
+    uint32_t key_a = 0, n_a = 0, total_a = 0;   // total_a: tokens of the row with key == key_a
     const bool use_k = top_k > 0 && top_k < V;
     if (use_k) {
         uint32_t prefix = 0, need = (uint32_t)top_k;
         for (int d = 3; d >= 0; --d) {
             if (tid < 256) chist[tid] = 0;
             __syncthreads();
-            for (int i = tid; i < V; i += ST) {
-                const uint32_t key = order_key(r.z[i]);
-                if (d == 3 || (key >> (8 * (d + 1))) == prefix) atomicAdd(&chist[(key >> (8 * d)) & 255u], 1u);
-            }
+            BinRun run{0, 0, 0, false};
+            for_whole_row(r.z, V, vec4, tid, [&](int, float z, bool ok) {
+                const uint32_t key = order_key(z);
+                if (ok && (d == 3 || (key >> (8 * (d + 1))) == prefix)) run_add(run, (key >> (8 * d)) & 255u, 0, chist, nullptr);
+            });
+            run_flush(run, chist, nullptr);
             __syncthreads();
-            if (tid == 0) {
-                uint32_t above = 0;
-                const int g = pick_bin<uint32_t>(chist, need, above);
-                sh_prefix = (prefix << 8) | (uint32_t)g;
-                sh_need = need - above;
+            if (wave == 0) {
+                uint32_t higher;
+                const int g = pick_bin<uint32_t>(chist, need, 0u, higher, lane);
+                if (lane == 0) {
+                    sh_prefix = (prefix << 8) | (uint32_t)g;
+                    sh_need = need - higher;
+                    sh_count_b = chist[g];   // after the last digit: every token of the row with exactly this key
+                }
             }
             __syncthreads();
             prefix = sh_prefix;
@@ -120,86 +223,86 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
             __syncthreads();
         }
         key_a = prefix;   // the key of the k-th token
-        n_a = need;       // 1 <= n_a <= number of tokens with that key
+        n_a = need;       // 1 <= n_a <= total_a
+        total_a = sh_count_b;
+        __syncthreads();
     }
 
-    // ---- Z_k ----
-    uint64_t part = 0;
-    for (int i = tid; i < V; i += ST) {
-        const float z = r.z[i];
-        if (!use_k || order_key(z) > key_a) part += fix_mass(r, z);
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
-    if (lane == 0) red_u[wave] = part;
-    __syncthreads();
-    uint64_t Zk = 0;
-    for (int w = 0; w < 16; ++w) Zk += red_u[w];
     // the n_a kept tokens at the top-k threshold all carry the same logit, hence the same mass
     uint64_t mass_a = 0;
     if (use_k) {
-        // recover the logit of key_a: invert order_key
-        const uint32_t u = (key_a & 0x80000000u) ? (key_a & 0x7FFFFFFFu) : ~key_a;
+        const uint32_t u = (key_a & 0x80000000u) ? (key_a & 0x7FFFFFFFu) : ~key_a;   // invert order_key
         mass_a = fix_mass(r, bits_f32(u));
-        Zk += (uint64_t)n_a * mass_a;
     }
-    __syncthreads();
 
-    // ---- top-p: key_b = key of the last token of S, n_b = how many tokens with exactly that key are in S ----
+    // ---- top-p: key_b = key of the last token of S, n_b = how many tokens with exactly that key are in S.
+    // The first pass's bins add up to Z_k, from which the target mass follows. ----
     uint32_t key_b = key_a, n_b = n_a;
-    uint64_t above_b = use_k ? Zk - (uint64_t)n_a * mass_a : 0;   // mass of the tokens of S with key > key_b
-    if (top_p < 1.f) {
-        uint64_t target = (uint64_t)((double)top_p * (double)Zk);
-        if (target < 1) target = 1;
-        if (target > Zk) target = Zk;
+    uint32_t count_b = n_a;   // kept tokens with key == key_b
+    uint32_t total_b = total_a;   // tokens of the row with key == key_b
+    {
+        const bool nucleus = top_p < 1.f;
+        uint64_t target = 0, above = 0;
         uint32_t prefix = 0;
-        uint64_t above = 0;
-        for (int d = 3; d >= 0; --d) {
+        for (int d = 3; nucleus && d >= 0; --d) {
             if (tid < 256) { mhist[tid] = 0; chist[tid] = 0; }
             __syncthreads();
-            for (int i = tid; i < V; i += ST) {
-                const float z = r.z[i];
+            BinRun run{0, 0, 0, false};
+            uint32_t *cbins = d == 0 ? chist : nullptr;   // counts matter only for the exact key (the ties at key_b)
+            for_whole_row(r.z, V, vec4, tid, [&](int, float z, bool ok) {
                 const uint32_t key = order_key(z);
-                if ((!use_k || key > key_a) && (d == 3 || (key >> (8 * (d + 1))) == prefix)) {
-                    const uint32_t g = (key >> (8 * d)) & 255u;
-                    atomicAdd((unsigned long long *)&mhist[g], (unsigned long long)fix_mass(r, z));
-                    atomicAdd(&chist[g], 1u);
-                }
-            }
+                if (ok && (!use_k || key > key_a) && (d == 3 || (key >> (8 * (d + 1))) == prefix))
+                    run_add(run, (key >> (8 * d)) & 255u, fix_mass(r, z), cbins, mhist);
+            });
+            run_flush(run, cbins, mhist);
             if (tid == 0 && use_k && (d == 3 || (key_a >> (8 * (d + 1))) == prefix)) {
                 const uint32_t g = (key_a >> (8 * d)) & 255u;
                 atomicAdd((unsigned long long *)&mhist[g], (unsigned long long)n_a * mass_a);
                 atomicAdd(&chist[g], n_a);
             }
             __syncthreads();
-            if (tid == 0) {
-                uint64_t ab = above;
-                const int g = pick_bin<uint64_t>(mhist, target, ab);
-                sh_prefix = (prefix << 8) | (uint32_t)g;
-                sh_above = ab;
-                sh_count_b = chist[g];
+            if (wave == 0) {
+                if (d == 3) {   // Z_k = the sum of all bins; the nucleus target follows from it
+                    uint64_t tot = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) tot += mhist[4 * lane + e];
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+                    target = (uint64_t)((double)top_p * (double)tot);
+                    if (target < 1) target = 1;
+                    if (target > tot) target = tot;
+                    if (lane == 0) { sh_total = tot; sh_target = target; }
+                }
+                if (nucleus) {
+                    uint64_t higher;
+                    const int g = pick_bin<uint64_t>(mhist, target, above, higher, lane);
+                    if (lane == 0) {
+                        sh_prefix = (prefix << 8) | (uint32_t)g;
+                        sh_above = above + higher;
+                        sh_count_b = chist[g];
+                    }
+                }
             }
             __syncthreads();
-            prefix = sh_prefix;
-            above = sh_above;
+            target = sh_target;
+            if (nucleus) {
+                prefix = sh_prefix;
+                above = sh_above;
+            }
             __syncthreads();
         }
-        key_b = prefix;
-        above_b = above;
-        const uint32_t avail = sh_count_b;   // kept tokens with key == key_b (after the last digit: exact key)
-        const uint32_t ub = (key_b & 0x80000000u) ? (key_b & 0x7FFFFFFFu) : ~key_b;
-        const uint64_t mass_b = fix_mass(r, bits_f32(ub));
-        uint64_t nb = mass_b ? (target - above + mass_b - 1) / mass_b : 1;
-        if (nb < 1) nb = 1;
-        if (nb > avail) nb = avail;
-        n_b = (uint32_t)nb;
-        // total of S below
-        sh_total = above_b + (uint64_t)n_b * mass_b;
-    } else {
-        sh_total = Zk;
+        if (nucleus) {
+            key_b = prefix;
+            count_b = sh_count_b;   // after the last digit: kept tokens with exactly this key
+            const uint32_t ub = (key_b & 0x80000000u) ? (key_b & 0x7FFFFFFFu) : ~key_b;
+            const uint64_t mass_b = fix_mass(r, bits_f32(ub));
+            uint64_t nb = mass_b ? (target - above + mass_b - 1) / mass_b : 1;
+            if (nb < 1) nb = 1;
+            if (nb > count_b) nb = count_b;
+            n_b = (uint32_t)nb;
+            total_b = (use_k && key_b == key_a) ? total_a : count_b;
+        }
     }
-    __syncthreads();
-    const uint64_t ZS = sh_total;
     const bool all_kept = !use_k && !(top_p < 1.f);   // S is the whole vocabulary
 
     // ---- sample in token-id order.  Wave w owns ids [w*per, (w+1)*per); lanes stride by 64. ----
@@ -207,66 +310,90 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
     const int lo = wave * per, hi = min(V, lo + per);
     // (1) ties at key_b below each wave, so that "the n_b lowest ids" is decidable per element
     uint32_t ties = 0;
-    if (!all_kept)
-        for (int base = lo; base < hi; base += 64) {
-            const int i = base + lane;
-            const bool tie = i < hi && order_key(r.z[i]) == key_b;
-            ties += (uint32_t)__popcll(__ballot(tie));
-        }
+    const bool partial_ties = !all_kept && n_b < total_b;   // else every tie is a member: no ranks needed
+    if (partial_ties)
+        for_row(r.z, lo, hi, lane, 64, [&](int, float z, bool ok) {
+            ties += (uint32_t)__popcll(__ballot(ok && order_key(z) == key_b));
+        });
     if (lane == 0) red_c[wave] = ties;
     __syncthreads();
     uint32_t tie_base = 0;
     for (int w = 0; w < wave; ++w) tie_base += red_c[w];
     // (2) mass of S inside each wave
-    auto member_mass = [&](int i, uint32_t &tie_seen) -> uint64_t {   // wave-uniform call; updates the running tie count
-        const float z = i < hi ? r.z[i] : 0.f;
+    auto member_mass = [&](float z, bool in_range, uint32_t &tie_seen) -> uint64_t {   // wave-uniform call; updates the running tie count
         const uint32_t key = order_key(z);
-        const bool in_range = i < hi;
         const bool tie = in_range && !all_kept && key == key_b;
-        const uint64_t bal = __ballot(tie);
-        const uint32_t rank = tie_seen + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-        tie_seen += (uint32_t)__popcll(bal);
+        uint32_t rank = 0;
+        if (partial_ties) {
+            const uint64_t bal = __ballot(tie);
+            rank = tie_seen + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+            tie_seen += (uint32_t)__popcll(bal);
+        }
         const bool member = in_range && (all_kept || key > key_b || (tie && rank < n_b));
         return member ? fix_mass(r, z) : 0ull;
     };
-    uint64_t wsum = 0;
+    // One entry per batch of 8 x 64 consecutive ids of every wave: the target is then located in one
+    // batch instead of a walk through the wave's whole range.
+    if (lane < MAX_BATCH) sub[wave][lane] = 0;   // ranges past the vocabulary leave their entries at zero
     {
         uint32_t seen = tie_base;
-        for (int base = lo; base < hi; base += 64) wsum += member_mass(base + lane, seen);
-    }
+        uint64_t bsum = 0;
+        int calls = 0, calls_total = 0;
+        for_row(r.z, lo, hi, lane, 64, [&](int, float z, bool ok) {
+            bsum += member_mass(z, ok, seen);
+            if (++calls == SU) {
+                uint64_t t = bsum;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) wsum += __shfl_xor(wsum, off);
-    if (lane == 0) red_u[wave] = wsum;
+                for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
+                const int batch = (calls_total++);
+                if (lane == 0) sub[wave][batch] = t;
+                calls = 0;
+                bsum = 0;
+            }
+        });
+    }
     __syncthreads();
-    // (3) the wave whose id range holds the target, then the element inside it
+    // (3) the (wave, batch) whose id range holds the target, then the element inside it
+    const int n_batch = (per + 64 * SU - 1) / (64 * SU);
     if (tid == 0) {
         uint64_t tot = 0;
-        for (int w = 0; w < 16; ++w) tot += red_u[w];
-        // tot equals ZS by construction; the draw uses the recomputed total so that it always lands inside
+        for (int w = 0; w < 16; ++w)
+            for (int bt = 0; bt < n_batch; ++bt) tot += sub[w][bt];
+        // the draw uses this recomputed total, so that it always lands inside S
         const double u = (double)uniforms[row];
         uint64_t target = (uint64_t)(u * (double)tot);
         if (target >= tot) target = tot ? tot - 1 : 0;
         uint64_t acc = 0;
-        int w = 0;
-        for (; w < 15; ++w) {
-            if (acc + red_u[w] > target) break;
-            acc += red_u[w];
-        }
+        int w = 0, bt = 0;
+        bool done = false;
+        for (w = 0; w < 16 && !done; ++w)
+            for (bt = 0; bt < n_batch; ++bt) {
+                if (acc + sub[w][bt] > target) { done = true; break; }
+                acc += sub[w][bt];
+            }
+        if (done) --w; else { w = 15; bt = n_batch - 1; }
         sh_wave = w;
-        sh_above = target - acc;   // offset of the target inside wave w's mass
+        sh_batch = bt;
+        sh_above = target - acc;   // offset of the target inside that batch
         sh_token = -1;
-        (void)ZS;
     }
     __syncthreads();
     if (wave == sh_wave) {
         const uint64_t target = sh_above;
-        uint64_t carry = 0;
+        const int b_lo = lo + sh_batch * 64 * SU, b_hi = min(hi, b_lo + 64 * SU);
+        // ties before this batch inside the wave's range (only needed when ties are taken partially)
         uint32_t seen = tie_base;
+        if (partial_ties)
+            for_row(r.z, lo, b_lo, lane, 64, [&](int, float z, bool ok) {
+                seen += (uint32_t)__popcll(__ballot(ok && order_key(z) == key_b));
+            });
+        uint64_t carry = 0;
         int found = -1;
         int last_member = -1;
-        for (int base = lo; base < hi && found < 0; base += 64) {
-            const int i = base + lane;
-            const uint64_t m = member_mass(i, seen);
+        for_row(r.z, b_lo, b_hi, lane, 64, [&](int i, float z, bool ok) {
+            if (found >= 0) return;                     // wave-uniform
+            const int base = i - lane;
+            const uint64_t m = member_mass(z, ok, seen);
             uint64_t inc = m;   // inclusive scan over lanes
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
@@ -279,7 +406,7 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
             if (mb) last_member = base + 63 - __clzll(mb);
             if (hb) found = base + __ffsll((long long)hb) - 1;
             carry += __shfl(inc, 63);
-        }
+        });
         if (lane == 0) sh_token = found >= 0 ? found : last_member;
     }
     __syncthreads();
@@ -299,6 +426,7 @@ __global__ __launch_bounds__(ST) void sample_rows_kernel(const float *logits, in
 hipError_t launch_sample_rows(const float *logits, int rows, int V, float temperature, int top_k, float top_p,
                               const float *uniforms, int32_t *sampled, hipStream_t s)
 {
+    if ((long)V > 16L * MAX_BATCH * 64 * SU) return hipErrorInvalidValue;
     hipLaunchKernelGGL(sample_rows_kernel, dim3(rows), dim3(ST), 0, s, logits, V, 1.f / temperature, top_k, top_p, uniforms,
                        sampled);
     return hipGetLastError();
