@@ -68,18 +68,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
     // Two register stages: while block i is processed out of LDS, block i+1 sits in one stage
     // (loaded during the previous iteration, moved to LDS at the end of this one) and block i+2 is
     // being fetched into the other, so two blocks (32 KiB with d = 128) are in flight per workgroup.
-    // Every load is issued unconditionally -- past the chunk's end it re-reads the last block, which
-    // is never stored -- because a load under a branch would make every later wait a full drain.
+    // Every load is issued unconditionally -- past the chunk's end all lanes re-read one record of the
+    // last block (a single cache line of traffic), which is never stored -- because a load under a
+    // branch would make every later wait a full drain.
     struct Stage {
         u32x4 k[SPT], v[SPT];
     };
     const int t_last = t_begin + ((t_end - t_begin - 1) & ~31);   // first position of the chunk's last block
     auto stage_load = [&](Stage &st, int t0) {
-        if (t0 > t_last) t0 = t_last;
+        const bool past = t0 > t_last;   // nothing left to fetch: every lane reads one and the same record
+        if (past) t0 = t_last;
 #pragma unroll
         for (int i = 0; i < SPT; ++i) {
             int rec = threadIdx.x + i * T;
             if (NREC % T != 0 && rec >= NREC) rec = NREC - 1;
+            if (past) rec = 0;
             st.k[i] = __builtin_nontemporal_load(Kc + (size_t)t0 * CPR + rec);
             st.v[i] = __builtin_nontemporal_load(Vc + (size_t)(t0 >> 5) * NREC + rec);
         }
