@@ -198,6 +198,27 @@ int sssd_verify_step_tree_sampled(sssd_ctx *ctx, int32_t B, int32_t k, const int
 int sssd_kv_commit_tree(sssd_ctx *ctx, int32_t B, int32_t k, int32_t *lens,
                         const int32_t *accepted_len, const int32_t *accepted_path, void *stream);
 
+/*
+ * Paged cache and continuous batching.  The cache of a layer is a pool of n_pages pages of
+ * rows_per_page = 32 positions (all kv heads of one sequence); kv_bytes of sssd_verify_sizes covers
+ * max_batch * blocks_per_seq pages, blocks_per_seq = ceil(max_seq / 32).  Without a block table
+ * sequence b owns pages b*blocks_per_seq .. (b+1)*blocks_per_seq - 1 (one contiguous run each: the
+ * behaviour described everywhere else in this header).  With a table, block i of sequence b
+ * (positions 32i .. 32i+31) lives in page block_table[b*blocks_per_seq + i] of every layer, so
+ * sequences of unequal length share the pool, and "sequence b" is whatever row b of the table says
+ * in THIS step: a serving loop that admits and retires sequences between steps (the batched
+ * serving the paper targets, Sec. 2 "Batching") only rewrites rows of the table and lens.
+ *   block_table  device int32 [max_batch][blocks_per_seq], or NULL to return to contiguous runs.
+ *                It is read on the device when each later call executes (steps, commit,
+ *                import/export, sssd_op_attention), so it may be updated in stream order between
+ *                calls; entries for blocks a step does not touch are ignored.  An entry outside
+ *                [0, n_pages) that a step would use is treated as in range (no fault) and raises the
+ *                sticky flag.  Two sequences of one step must not share a page they write.
+ */
+int sssd_kv_geometry(const sssd_model_config *cfg, int32_t *rows_per_page, int32_t *blocks_per_seq,
+                     int32_t *n_pages);
+int sssd_kv_set_block_table(sssd_ctx *ctx, const int32_t *block_table);
+
 /* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call raised
  * the device flag (and clear it), else SSSD_OK. */
 int sssd_verify_sync(sssd_ctx *ctx, void *stream);

@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
         l.sssd_verify_step_tree_sampled.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(SamplingParams), vp, vp, vp, vp, vp, vp]
         l.sssd_op_sample.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
+        l.sssd_kv_geometry.argtypes = [C.POINTER(ModelConfig), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        l.sssd_kv_set_block_table.argtypes = [vp, vp]
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
         l.sssd_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         l.sssd_kv_export.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
@@ -117,6 +119,12 @@ def sssd_verify_sizes(cfg: ModelConfig):
     kv, ws, pk = C.c_size_t(), C.c_size_t(), C.c_size_t()
     _check(lib().sssd_verify_sizes(C.byref(cfg), C.byref(kv), C.byref(ws), C.byref(pk)), "sssd_verify_sizes")
     return kv.value, ws.value, pk.value
+
+
+def sssd_kv_geometry(cfg: ModelConfig):
+    rows, bps, pages = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().sssd_kv_geometry(C.byref(cfg), C.byref(rows), C.byref(bps), C.byref(pages)), "sssd_kv_geometry")
+    return rows.value, bps.value, pages.value
 
 
 class VerifyContext:
@@ -194,6 +202,12 @@ class VerifyContext:
                          new_lens: Optional[torch.Tensor] = None) -> None:
         _check(lib().sssd_kv_rollback(self.handle, lens.numel(), _ptr(lens), _ptr(accepted_len), _ptr(new_lens),
                                       _stream()), "sssd_kv_rollback")
+
+    def sssd_kv_set_block_table(self, block_table: Optional[torch.Tensor]) -> None:
+        if block_table is not None:
+            assert block_table.dtype == torch.int32
+        self._block_table = block_table          # keep the tensor alive while the library reads it
+        _check(lib().sssd_kv_set_block_table(self.handle, _ptr(block_table)), "sssd_kv_set_block_table")
 
     def sssd_verify_sync(self) -> int:
         return lib().sssd_verify_sync(self.handle, _stream())

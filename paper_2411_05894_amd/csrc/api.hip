@@ -52,6 +52,7 @@ struct sssd_ctx {
     std::vector<LayerW> layers;
     const uint16_t *embed, *lm_head, *final_norm;
     uint16_t *Kc, *Vc;
+    const int32_t *block_table;   // device [max_batch][blocks_per_seq] or nullptr (contiguous runs of pages)
     float *dbg_logits, *dbg_hidden;
     bool prof_on;
     std::vector<ProfEvent> prof_pool;
@@ -89,6 +90,8 @@ Dims make_dims(const sssd_model_config *c)
     D.qd = D.nq * D.d; D.kd = D.nkv * D.d; D.g = D.nq / D.nkv;
     D.max_batch = c->max_batch; D.max_k = c->max_k; D.max_seq = c->max_seq;
     D.seq_pad = round_up(c->max_seq, 32);
+    D.blocks_per_seq = D.seq_pad / 32;
+    D.n_pages = D.max_batch * D.blocks_per_seq;
     D.eps = c->rms_eps; D.rope_base = c->rope_base;
     return D;
 }
@@ -220,6 +223,8 @@ int drain_prof(sssd_ctx *c)
 
 bool valid(const sssd_ctx *c) { return c && c->magic == MAGIC; }
 
+KvGeom kv_geom(const sssd_ctx *c) { return KvGeom{c->block_table, c->D.blocks_per_seq, c->D.n_pages, c->D.nkv, c->D.d}; }
+
 }  // namespace
 
 extern "C" {
@@ -286,6 +291,7 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
     c->embed = (const uint16_t *)w->embed;
     c->final_norm = (const uint16_t *)w->final_norm;
     c->dbg_logits = c->dbg_hidden = nullptr;
+    c->block_table = nullptr;
     c->prof_on = false;
     c->prof_used = 0;
     for (int i = 0; i < SSSD_PROF_CLASSES; ++i) { c->prof_ms[i] = 0; c->prof_n[i] = 0; }
@@ -408,12 +414,12 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
     // after every GEMM whose K is split over workgroups.
     {
         Prof p(c, s, SSSD_PROF_ELEM);
-        HIP_TRY(launch_fused_embed(D, io, c->embed, c->layers[0].attn_norm, W.X, W.Ah_hi, W.Ah_lo, W.ssq1, W.pos_base,
+        HIP_TRY(launch_fused_embed(D, io, kv_geom(c), c->embed, c->layers[0].attn_norm, W.X, W.Ah_hi, W.Ah_lo, W.ssq1, W.pos_base,
                                    W.rope_pos, W.anc, W.err_flag, s));
     }
     FusedGemmArgs f{};
     f.M = M; f.h = D.h; f.d = D.d; f.nq = D.nq; f.nkv = D.nkv; f.seq_pad = D.seq_pad; f.k = k;
-    f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps;
+    f.q_rows_pad = c->S.q_rows_pad; f.vocab = D.V; f.eps = D.eps; f.kv = kv_geom(c);
     f.X = W.X; f.rope_cs = W.rope_cs; f.pos_base = W.pos_base; f.rope_pos = W.rope_pos; f.Qp = W.Qp; f.Qp_lo = W.Qp_lo;
     f.logits = smp ? smp->logits : c->dbg_logits; f.part_val = W.part_val; f.part_idx = W.part_idx;
     const int KTh = (D.h + 31) / 32, KTq = (D.qd + 31) / 32, KTf = (D.f + 31) / 32;
@@ -438,7 +444,7 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
         f.n_units = (D.nq + 2 * D.nkv) * (D.d / 32); f.Ntot = D.qd + 2 * D.kd;
         HIP_TRY(fgemm(FEPI_QKV));
         {
-            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
+            AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, kv_geom(c), W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
             Prof p(c, s, SSSD_PROF_ATTN);
             HIP_TRY(launch_attention(D, a, s));
         }
@@ -517,8 +523,26 @@ int sssd_kv_commit_tree(sssd_ctx *c, int32_t B, int32_t k, int32_t *lens, const 
     if (!valid(c) || !lens || !accepted_len || !accepted_path) return SSSD_EINVAL;
     if (B <= 0 || k < 0) return SSSD_EINVAL;
     if (B > c->D.max_batch || k > c->D.max_k) return SSSD_ECAPACITY;
-    HIP_TRY(launch_kv_compact(c->D, c->Kc, c->Vc, c->S.kv_layer_elems, B, k, lens, accepted_len, accepted_path,
+    HIP_TRY(launch_kv_compact(c->D, kv_geom(c), c->Kc, c->Vc, c->S.kv_layer_elems, B, k, lens, accepted_len, accepted_path,
                               c->W.err_flag, (hipStream_t)stream));
+    return SSSD_OK;
+}
+
+int sssd_kv_geometry(const sssd_model_config *cfg, int32_t *rows_per_page, int32_t *blocks_per_seq, int32_t *n_pages)
+{
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    const Dims D = make_dims(cfg);
+    if (rows_per_page) *rows_per_page = 32;
+    if (blocks_per_seq) *blocks_per_seq = D.blocks_per_seq;
+    if (n_pages) *n_pages = D.n_pages;
+    return SSSD_OK;
+}
+
+int sssd_kv_set_block_table(sssd_ctx *c, const int32_t *block_table)
+{
+    if (!valid(c)) return SSSD_EINVAL;
+    c->block_table = block_table;
     return SSSD_OK;
 }
 
@@ -554,8 +578,8 @@ static int kv_copy(sssd_ctx *c, int32_t layer, int32_t b, int32_t t0, int32_t n_
     const Dims &D = c->D;
     if (layer < 0 || layer >= D.L || b < 0 || b >= D.max_batch || t0 < 0 || n_rows < 0) return SSSD_EINVAL;
     if ((long)t0 + n_rows > D.max_seq) return SSSD_ECAPACITY;
-    const size_t off = (size_t)layer * c->S.kv_layer_elems + (size_t)b * D.nkv * D.seq_pad * D.d;
-    HIP_TRY(launch_kv_copy(D, c->Kc + off, c->Vc + off, t0, n_rows, (uint16_t *)k_ext, (uint16_t *)v_ext, import,
+    const size_t off = (size_t)layer * c->S.kv_layer_elems;
+    HIP_TRY(launch_kv_copy(D, kv_geom(c), c->Kc + off, c->Vc + off, b, t0, n_rows, (uint16_t *)k_ext, (uint16_t *)v_ext, import,
                            (hipStream_t)stream));
     return SSSD_OK;
 }
@@ -669,7 +693,7 @@ int sssd_op_attention(sssd_ctx *c, int32_t layer, int32_t B, int32_t k, const fl
     HIP_TRY(launch_lens(D, B, k, lens, W.pos_base, W.rope_pos, W.anc, W.err_flag, s));
     HIP_TRY(launch_q_pack(D, q, B, k, W.Qp, W.Qp_lo, s));
     uint16_t *Kl = c->Kc + (size_t)layer * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)layer * c->S.kv_layer_elems;
-    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
+    AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, kv_geom(c), W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
     HIP_TRY(launch_attention(D, a, s));
     HIP_TRY(launch_unpack_act(W.Aq_hi, W.Aq_lo, B * (k + 1), D.qd, out, s));
     return SSSD_OK;

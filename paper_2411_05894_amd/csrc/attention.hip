@@ -57,9 +57,26 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
     if (t_begin >= total) return;
     const int t_end = min(total, t_begin + a.chunk);
 
-    const size_t slab = ((size_t)b * D.nkv + kvh) * D.seq_pad * HD;
-    const u32x4 *Kc = reinterpret_cast<const u32x4 *>(a.Kc + slab);
-    const u32x4 *Vc = reinterpret_cast<const u32x4 *>(a.Vc + slab);
+    // Pages of the chunk's blocks: lane l keeps the page of block first_blk + 64*group + l, so the
+    // page of any block of the current group of 64 is one cross-lane read away.
+    const u32x4 *Kpool = reinterpret_cast<const u32x4 *>(a.Kc), *Vpool = reinterpret_cast<const u32x4 *>(a.Vc);
+    const int first_blk = t_begin >> 5;
+    int pg_group = 0;
+    auto load_pages = [&](int group) {
+        const int blk = min(first_blk + 64 * group + lane, a.kv.blocks_per_seq - 1);
+        return kv_page(a.kv, b, blk);
+    };
+    int pg = load_pages(0);
+    // 16-byte record offset of block (t0 / 32) of this (sequence, kv head) in either pool
+    auto block_records = [&](int t0) -> size_t {
+        const int rel = (t0 >> 5) - first_blk;
+        if ((rel >> 6) != pg_group) {   // wave-uniform, once per 64 blocks
+            pg_group = rel >> 6;
+            pg = load_pages(pg_group);
+        }
+        const int page = __shfl(pg, rel & 63);
+        return (((size_t)page * D.nkv + kvh) * 32 * HD) >> 3;
+    };
     const int rt = rt_base + wave;
     const u32x4 *Qs = reinterpret_cast<const u32x4 *>(a.Qp + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD) + (size_t)rt * KS * 64 + lane;
     const u32x4 *Ql = reinterpret_cast<const u32x4 *>(a.Qp_lo + ((size_t)b * D.nkv + kvh) * q_rows_pad * HD) + (size_t)rt * KS * 64 + lane;
@@ -78,13 +95,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
     auto stage_load = [&](Stage &st, int t0) {
         const bool past = t0 > t_last;   // nothing left to fetch: every lane reads one and the same record
         if (past) t0 = t_last;
+        const size_t base = block_records(t0);
 #pragma unroll
         for (int i = 0; i < SPT; ++i) {
             int rec = threadIdx.x + i * T;
             if (NREC % T != 0 && rec >= NREC) rec = NREC - 1;
             if (past) rec = 0;
-            st.k[i] = __builtin_nontemporal_load(Kc + (size_t)t0 * CPR + rec);
-            st.v[i] = __builtin_nontemporal_load(Vc + (size_t)(t0 >> 5) * NREC + rec);
+            st.k[i] = __builtin_nontemporal_load(Kpool + base + rec);
+            st.v[i] = __builtin_nontemporal_load(Vpool + base + rec);
         }
     };
     auto stage_store = [&](int buf, const Stage &st) {

@@ -53,18 +53,51 @@ __host__ __device__ __forceinline__ size_t packed_index(int r, int k, int KT)
     return ((((size_t)(r >> 4) * KT + (k >> 5)) * 64 + (size_t)(((k & 31) >> 3) * 16 + (r & 15))) << 3) + (k & 7);
 }
 
-// ---- V cache order -------------------------------------------------------------
-// V of one (layer, sequence, kv head) is stored in blocks of 32 positions; a
-// block holds head_dim/16 operand tiles of 1 KiB.  Lane l = 16*q + c of tile dt
-// holds channel dt*16 + c at the 8 positions {4q..4q+3} u {16+4q..16+4q+3} of the
-// block: exactly the positions whose scores that lane owns after the two
-// 16-position score MFMAs, so probabilities feed the second MFMA without any
-// cross-lane movement.  bf16 index of (t, ch) within the (layer, b, head) slab:
-__host__ __device__ __forceinline__ size_t vcache_index(int t, int ch, int head_dim)
+// ---- KV cache: pages of 32 positions ---------------------------------------------
+// The cache of one layer is a pool of pages; a page holds 32 consecutive positions of ONE sequence for
+// all kv heads: K as [kv head][32 rows][head_dim] (row-major), V as [kv head][head_dim/16 operand
+// tiles of 1 KiB].  Block i of sequence b (positions 32i .. 32i+31) lives in page table[b][i], or in
+// page b * blocks_per_seq + i when no table is set (every sequence then owns a contiguous run of
+// pages).  A (sequence, kv head, block) is 32*head_dim contiguous bf16 in both caches: the unit the
+// attention kernel streams.
+//
+// Within a V block, lane l = 16*q + c of tile dt holds channel dt*16 + c at the 8 positions
+// {4q..4q+3} u {16+4q..16+4q+3} of the block: exactly the positions whose scores that lane owns
+// after the two 16-position score MFMAs, so probabilities feed the second MFMA without any
+// cross-lane movement.  bf16 index of (row r of the block, channel ch) within the block:
+__host__ __device__ __forceinline__ size_t vblock_index(int r, int ch, int head_dim)
 {
-    int tb = t >> 5, tt = t & 31;
-    int q = (tt & 15) >> 2, e = (tt & 3) + ((tt >> 4) << 2);
-    return ((((size_t)tb * (head_dim >> 4) + (ch >> 4)) * 64 + (size_t)(q * 16 + (ch & 15))) << 3) + e;
+    (void)head_dim;
+    const int q = (r & 15) >> 2, e = (r & 3) + ((r >> 4) << 2);
+    return ((((size_t)(ch >> 4)) * 64 + (size_t)(q * 16 + (ch & 15))) << 3) + e;
+}
+
+struct KvGeom {
+    const int32_t *table;   // device [max_batch][blocks_per_seq], or nullptr: contiguous runs
+    int blocks_per_seq, n_pages, nkv, d;
+};
+// Page of block blk of sequence b, forced into the pool (a bad table entry is reported by the
+// embedding kernel; here it only must not fault).
+__device__ __forceinline__ int kv_page(const KvGeom &g, int b, int blk)
+{
+    int page = g.table ? g.table[(size_t)b * g.blocks_per_seq + blk] : b * g.blocks_per_seq + blk;
+    if (page < 0) page = 0;
+    if (page >= g.n_pages) page = g.n_pages - 1;
+    return page;
+}
+// bf16 offset of the (page, kv head) block inside a layer's K or V pool
+__device__ __forceinline__ size_t kv_block_offset(const KvGeom &g, int page, int kvh)
+{
+    return ((size_t)page * g.nkv + kvh) * 32 * g.d;
+}
+// bf16 offsets of element (position t, channel ch) of (sequence b, kv head kvh)
+__device__ __forceinline__ size_t kcache_offset(const KvGeom &g, int b, int kvh, int t, int ch)
+{
+    return kv_block_offset(g, kv_page(g, b, t >> 5), kvh) + (size_t)(t & 31) * g.d + ch;
+}
+__device__ __forceinline__ size_t vcache_offset(const KvGeom &g, int b, int kvh, int t, int ch)
+{
+    return kv_block_offset(g, kv_page(g, b, t >> 5), kvh) + vblock_index(t & 31, ch, g.d);
 }
 
 // Model dimensions and buffer map handed to every kernel launcher.
@@ -72,6 +105,7 @@ struct Dims {
     int L, h, nq, nkv, d, f, V;
     int qd, kd, g;       // nq*d, nkv*d, nq/nkv
     int max_batch, max_k, max_seq, seq_pad;  // seq_pad = max_seq rounded up to 32
+    int blocks_per_seq, n_pages;             // KV pages of 32 positions: per sequence, in the pool
     float eps, rope_base;
 };
 

@@ -77,22 +77,21 @@ __global__ void accept_tree_kernel(StepIO io, const int32_t *that)
 // grid = (nkv, B, L), block = d threads.  Thread i moves channel i of the accepted rows, one row
 // after the other in path order: destinations lens + 1 .. lens + n never run ahead of the sources
 // still to be read (path[i] >= i, increasing), and each thread touches its own channel only.
-__global__ void kv_compact_kernel(Dims D, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int k, const int32_t *lens,
+__global__ void kv_compact_kernel(Dims D, KvGeom kv, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int k, const int32_t *lens,
                                   const int32_t *accepted_len, const int32_t *path)
 {
     const int kvh = blockIdx.x, b = blockIdx.y, l = blockIdx.z, i = threadIdx.x;
     const int len = lens[b], n = accepted_len[b];
     if (len < 0 || n < 0 || n > k || len + k + 1 > D.max_seq) return;   // flagged by kv_commit_kernel
-    const size_t slab = (size_t)l * kv_layer_elems + ((size_t)b * D.nkv + kvh) * D.seq_pad * D.d;
-    uint16_t *kc = Kc + slab, *vc = Vc + slab;
+    uint16_t *kc = Kc + (size_t)l * kv_layer_elems, *vc = Vc + (size_t)l * kv_layer_elems;
     int prev = 0;
     for (int s = 1; s <= n; ++s) {
         const int node = path[b * (k + 1) + s];
         if (node <= prev || node > k) return;        // not an increasing path: leave the rest alone (flagged)
         prev = node;
         if (node == s) continue;
-        kc[(size_t)(len + s) * D.d + i] = kc[(size_t)(len + node) * D.d + i];
-        vc[vcache_index(len + s, i, D.d)] = vc[vcache_index(len + node, i, D.d)];
+        kc[kcache_offset(kv, b, kvh, len + s, i)] = kc[kcache_offset(kv, b, kvh, len + node, i)];
+        vc[vcache_offset(kv, b, kvh, len + s, i)] = vc[vcache_offset(kv, b, kvh, len + node, i)];
     }
 }
 
@@ -123,14 +122,15 @@ __global__ void rollback_kernel(int B, int32_t *lens, const int32_t *accepted_le
     else lens[b] = new_lens[b];
 }
 
-// grid = (n_rows, nkv), block = d.  ext layout [nkv][n_rows][d].
-__global__ void kv_copy_kernel(Dims D, uint16_t *Kc, uint16_t *Vc, int t0, int n_rows, uint16_t *k_ext, uint16_t *v_ext,
-                               bool import)
+// grid = (n_rows, nkv), block = d.  ext layout [nkv][n_rows][d]; Kc/Vc: the layer's pools.
+__global__ void kv_copy_kernel(Dims D, KvGeom kv, uint16_t *Kc, uint16_t *Vc, int b, int t0, int n_rows, uint16_t *k_ext,
+                               uint16_t *v_ext, bool import)
 {
+    (void)D;
     const int t = blockIdx.x, kvh = blockIdx.y, i = threadIdx.x;
-    uint16_t *kc = Kc + ((size_t)kvh * D.seq_pad + t0 + t) * D.d + i;
-    uint16_t *vc = Vc + (size_t)kvh * D.seq_pad * D.d + vcache_index(t0 + t, i, D.d);
-    const size_t e = ((size_t)kvh * n_rows + t) * D.d + i;
+    uint16_t *kc = Kc + kcache_offset(kv, b, kvh, t0 + t, i);
+    uint16_t *vc = Vc + vcache_offset(kv, b, kvh, t0 + t, i);
+    const size_t e = ((size_t)kvh * n_rows + t) * kv.d + i;
     if (import) {
         *kc = k_ext[e];
         *vc = v_ext[e];
@@ -220,7 +220,7 @@ __global__ void pack_weight_kernel(const uint16_t *src, u32x4 *dst, int N, int K
 
 // grid = M rows, 512 threads.  Validates lens/tokens/parents; row geometry (depth and visible new
 // rows of the node, from the draft tree or the chain); x = E[token]; packed x*gamma; sums of squares.
-__global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, const uint16_t *embed, const uint16_t *gamma,
+__global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, KvGeom kv, const uint16_t *embed, const uint16_t *gamma,
                                                           float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq,
                                                           int32_t *pos_base, int32_t *rope_pos, uint32_t *anc,
                                                           int32_t *err_flag)
@@ -237,7 +237,16 @@ __global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, con
             *err_flag = 1;
             len = 0;
         }
-        if (j == 0) pos_base[b] = len;
+        if (j == 0) {
+            pos_base[b] = len;
+            if (kv.table) {   // every page the step reads or writes must lie in the pool
+                const int last_blk = (len + io.k) >> 5;
+                for (int blk = 0; blk <= last_blk; ++blk) {
+                    const int page = kv.table[(size_t)b * kv.blocks_per_seq + blk];
+                    if (page < 0 || page >= kv.n_pages) *err_flag = 1;
+                }
+            }
+        }
         int depth = j;
         uint32_t vis = 0xFFFFFFFFu >> (31 - j);
         if (io.parents) {
@@ -297,23 +306,23 @@ hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, co
     return hipGetLastError();
 }
 
-hipError_t launch_kv_compact(const Dims &D, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int B, int k, int32_t *lens,
-                             const int32_t *accepted_len, const int32_t *path, int32_t *err_flag, hipStream_t s)
+hipError_t launch_kv_compact(const Dims &D, const KvGeom &kv, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int B, int k,
+                             int32_t *lens, const int32_t *accepted_len, const int32_t *path, int32_t *err_flag, hipStream_t s)
 {
-    hipLaunchKernelGGL(kv_compact_kernel, dim3(D.nkv, B, D.L), dim3(D.d), 0, s, D, Kc, Vc, kv_layer_elems, k, lens, accepted_len,
-                       path);
+    hipLaunchKernelGGL(kv_compact_kernel, dim3(D.nkv, B, D.L), dim3(D.d), 0, s, D, kv, Kc, Vc, kv_layer_elems, k, lens,
+                       accepted_len, path);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kv_commit_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, accepted_len, path, err_flag);
     return hipGetLastError();
 }
 
-hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, int t0, int n_rows, uint16_t *k_ext,
-                          uint16_t *v_ext, bool import, hipStream_t s)
+hipError_t launch_kv_copy(const Dims &D, const KvGeom &kv, uint16_t *Kc_layer, uint16_t *Vc_layer, int b, int t0, int n_rows,
+                          uint16_t *k_ext, uint16_t *v_ext, bool import, hipStream_t s)
 {
     if (n_rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(kv_copy_kernel, dim3(n_rows, D.nkv), dim3(D.d), 0, s, D, Kc_slab, Vc_slab, t0, n_rows, k_ext, v_ext,
-                       import);
+    hipLaunchKernelGGL(kv_copy_kernel, dim3(n_rows, D.nkv), dim3(D.d), 0, s, D, kv, Kc_layer, Vc_layer, b, t0, n_rows, k_ext,
+                       v_ext, import);
     return hipGetLastError();
 }
 
@@ -353,11 +362,11 @@ hipError_t launch_pack_weight(const uint16_t *src, uint16_t *dst, int N, int K, 
     return hipGetLastError();
 }
 
-hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
-                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos, uint32_t *anc,
-                              int32_t *err_flag, hipStream_t s)
+hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const KvGeom &kv, const uint16_t *embed, const uint16_t *gamma,
+                              float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos,
+                              uint32_t *anc, int32_t *err_flag, hipStream_t s)
 {
-    hipLaunchKernelGGL(fused_embed_kernel, dim3(io.B * (io.k + 1)), dim3(512), 0, s, D, io, embed, gamma, X, A_hi, A_lo, ssq,
+    hipLaunchKernelGGL(fused_embed_kernel, dim3(io.B * (io.k + 1)), dim3(512), 0, s, D, io, kv, embed, gamma, X, A_hi, A_lo, ssq,
                        pos_base, rope_pos, anc, err_flag);
     return hipGetLastError();
 }

@@ -43,7 +43,8 @@ struct FusedGemmArgs {
     const float *rope_cs;         // QKV
     const int32_t *pos_base;      // QKV: cache row of (b, j) is pos_base[b] + j
     const int32_t *rope_pos;      // QKV: rotary position of row m
-    uint16_t *Qp, *Qp_lo, *Kc, *Vc;  // Kc, Vc: this layer's cache
+    uint16_t *Qp, *Qp_lo, *Kc, *Vc;  // Kc, Vc: this layer's cache pools
+    KvGeom kv;                    // QKV: page geometry of the cache
     float *logits, *part_val;     // LM
     int *part_idx;
     // weight streamer (stream_gemm.hip)
@@ -67,8 +68,8 @@ size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-lev
 hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,
                               hipEvent_t t1);
 hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s);
-hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const uint16_t *embed, const uint16_t *gamma, float *X,
-                              uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos,
+hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const KvGeom &kv, const uint16_t *embed, const uint16_t *gamma,
+                              float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos,
                               uint32_t *anc, int32_t *err_flag, hipStream_t s);
 
 // Merge per-tile arg-max partials, then greedy acceptance (longest matching prefix of a chain, or
@@ -84,10 +85,10 @@ hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, co
                            hipStream_t s);
 // Tree commit: in every layer move the K/V rows of the accepted nodes path[b][1..n] from cache rows
 // lens[b] + path[b][i] to lens[b] + i, then lens[b] += n + 1.  Kc/Vc: whole cache (all layers).
-hipError_t launch_kv_compact(const Dims &D, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int B, int k,
+hipError_t launch_kv_compact(const Dims &D, const KvGeom &kv, uint16_t *Kc, uint16_t *Vc, size_t kv_layer_elems, int B, int k,
                              int32_t *lens, const int32_t *accepted_len, const int32_t *path, int32_t *err_flag,
                              hipStream_t s);
-hipError_t launch_kv_copy(const Dims &D, uint16_t *Kc_slab, uint16_t *Vc_slab, int t0, int n_rows,
+hipError_t launch_kv_copy(const Dims &D, const KvGeom &kv, uint16_t *Kc_layer, uint16_t *Vc_layer, int b, int t0, int n_rows,
                           uint16_t *k_ext, uint16_t *v_ext, bool import, hipStream_t s);
 
 // Kernel-level entry points only (parity tests, micro-benchmarks).
@@ -101,7 +102,8 @@ hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t
 struct AttnArgs {
     const uint16_t *Qp;        // packed Q (bf16 hi part), one slab of q_rows_pad x d per (b, kv head)
     const uint16_t *Qp_lo;     // bf16 lo part: q ~= hi + lo
-    const uint16_t *Kc, *Vc;   // this layer's cache
+    const uint16_t *Kc, *Vc;   // this layer's cache pools
+    KvGeom kv;                 // page geometry
     const int32_t *pos_base;   // validated lens
     const uint32_t *anc;       // [B*(k+1)] visible new rows of each query row (bit i = row pos_base + i)
     float *part_o;             // [b][kv head][n_splits][q_rows_pad][d]

@@ -106,7 +106,6 @@ __device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m
         const int b = m / (a.k + 1), j = m % (a.k + 1);
         const int pos = a.pos_base[b] + j;              // cache row of node j
         const int half = a.d >> 1, ch = pair * 16 + c;  // channel of v0; v1 is ch + half
-        const size_t slab = (size_t)b * a.nkv * a.seq_pad * a.d;
         if (head < a.nq + a.nkv) {
             const float2 cs = *reinterpret_cast<const float2 *>(a.rope_cs + ((size_t)a.rope_pos[m] * half + ch) * 2);
             const float y0 = v0 * cs.x - v1 * cs.y, y1 = v0 * cs.y + v1 * cs.x;
@@ -121,15 +120,15 @@ __device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m
                 a.Qp[i_1] = h1; a.Qp_lo[i_1] = l1;
             } else {
                 head -= a.nq;
-                uint16_t *kr = a.Kc + slab + ((size_t)head * a.seq_pad + pos) * a.d;
+                uint16_t *kr = a.Kc + kcache_offset(a.kv, b, head, pos, 0);
                 kr[ch] = f32_to_bf16(y0);
                 kr[ch + half] = f32_to_bf16(y1);
             }
         } else {
             head -= a.nq + a.nkv;
-            uint16_t *vv = a.Vc + slab + (size_t)head * a.seq_pad * a.d;
-            vv[vcache_index(pos, ch, a.d)] = f32_to_bf16(v0);
-            vv[vcache_index(pos, ch + half, a.d)] = f32_to_bf16(v1);
+            uint16_t *vv = a.Vc + kv_block_offset(a.kv, kv_page(a.kv, b, pos >> 5), head);
+            vv[vblock_index(pos & 31, ch, a.d)] = f32_to_bf16(v0);
+            vv[vblock_index(pos & 31, ch + half, a.d)] = f32_to_bf16(v1);
         }
     } else if (EPI == FEPI_SWIGLU) {
         if (!valid) return;
@@ -432,7 +431,6 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int blocks_pe
                 const int ch = col - head * a.d;              // first-half channel of v0[0]
                 const int b = m / (a.k + 1), j = m % (a.k + 1);
                 const int pos = a.pos_base[b] + j;            // cache row of node j
-                const size_t slab = (size_t)b * a.nkv * a.seq_pad * a.d;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { v0.v[e] *= rs; v1.v[e] *= rs; }
                 if (head < a.nq + a.nkv) {
@@ -456,17 +454,17 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int blocks_pe
                         *reinterpret_cast<u32x4 *>(a.Qp + i_1) = h1; *reinterpret_cast<u32x4 *>(a.Qp_lo + i_1) = l1;
                     } else {
                         head -= a.nq;
-                        uint16_t *kr = a.Kc + slab + ((size_t)head * a.seq_pad + pos) * a.d;
+                        uint16_t *kr = a.Kc + kcache_offset(a.kv, b, head, pos, 0);
                         *reinterpret_cast<u32x4 *>(kr + ch) = round8(y0);
                         *reinterpret_cast<u32x4 *>(kr + ch + half) = round8(y1);
                     }
                 } else {
                     head -= a.nq + a.nkv;
-                    uint16_t *vv = a.Vc + slab + (size_t)head * a.seq_pad * a.d;
+                    uint16_t *vv = a.Vc + kv_block_offset(a.kv, kv_page(a.kv, b, pos >> 5), head);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        vv[vcache_index(pos, ch + e, a.d)] = f32_to_bf16(v0.v[e]);
-                        vv[vcache_index(pos, ch + half + e, a.d)] = f32_to_bf16(v1.v[e]);
+                        vv[vblock_index(pos & 31, ch + e, a.d)] = f32_to_bf16(v0.v[e]);
+                        vv[vblock_index(pos & 31, ch + half + e, a.d)] = f32_to_bf16(v1.v[e]);
                     }
                 }
             }
