@@ -93,6 +93,32 @@ def test_cfg2_shape_draft_tree_k16(pair_8b):
 
 
 @pytest.mark.timeout(300)
+def test_cfg2_shape_paged_cache_is_bit_identical(pair_8b):
+    """The 8B shape at B=1, context 2048, k=8 with the sequence's 65 blocks scattered over the pool by a
+    block table: the logits must equal the contiguous run's bit for bit (same kernels, same launch
+    configuration; only the page addresses differ)."""
+    p, s = pair_8b, pair_8b.shape
+    k = 8
+    tokens = uniform_int(4, TensorId.TOKENS, (1, k + 1), 0, s.vocab - 1)
+    lens = torch.tensor([2048], dtype=torch.int32)
+    p.prefill_random_kv(4, 0, 2048)
+    a = p.step(tokens, lens)["logits"].clone()
+    rows, bps, n_pages = sv.sssd_kv_geometry(p.cfg)
+    keys = uniform_int(7, 1, (n_pages,), 0, 1 << 30).tolist()
+    perm = sorted(range(n_pages), key=lambda i: (keys[i], i))
+    table = torch.tensor(perm[: 32 * bps], dtype=torch.int32).view(32, bps).to(DEV)
+    try:
+        p.ctx.sssd_kv_set_block_table(table)
+        p.prefill_random_kv(4, 0, 2048)                   # the same rows, imported through the table
+        b = p.step(tokens, lens)["logits"]
+        assert torch.equal(a, b)
+        progress(f"cfg2-paged: {bps} blocks of sequence 0 scattered over {n_pages} pages, logits bit-identical")
+    finally:
+        p.ctx.sssd_kv_set_block_table(None)
+        p.prefill_random_kv(4, 0, 2048)                   # pages of other sequences were overwritten: restore slot 0
+
+
+@pytest.mark.timeout(300)
 def test_cfg3_8b_b32_ragged_k4(pair_8b):
     """Config 3: B=32, context lengths uniform in [1024, 4096], k=4.  Sequences 5 and 31 are
     recomputed by the oracle."""
