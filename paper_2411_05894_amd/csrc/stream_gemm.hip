@@ -195,8 +195,9 @@ __device__ __forceinline__ void stream_tile(const u32x4 (&ah)[MT][KPW], const u3
 
 // grid = n_groups * J workgroups of 1024 threads; MT row tiles of 16 (M <= 16*MT).  Workgroup
 // (grp, j) computes units [grp*upw, (grp+1)*upw) over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1
-// it stores fp32 partial tiles for epi_kernel instead of applying the epilogue.
-template <int EPI, int KPW, int MT>
+// (SPLIT) it stores fp32 partial tiles for epi_kernel instead of applying the epilogue, and the
+// unsplit instantiation carries none of that code (the QKV kernel is at the register limit).
+template <int EPI, int KPW, int MT, bool SPLIT>
 __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 {
     constexpr int TPU = Unit<EPI>::TILES;
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
     __shared__ float red[NBUF][PW][MT * 256];
     __shared__ float rstd_s[MT * 16];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int J = a.J, j = blockIdx.x % J, grp = blockIdx.x / J;
+    const int J = SPLIT ? a.J : 1, j = SPLIT ? blockIdx.x % J : 0, grp = SPLIT ? blockIdx.x / J : blockIdx.x;
     const int KT = a.KT;
     const int kt0 = (j * PW + wave) * KPW;
     // Units grp, grp + groups, grp + 2*groups, ... so that at any time the workgroups of a launch
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
             ah[mt][i] = live ? a.A_hi[at] : u32x4{0, 0, 0, 0};
             al[mt][i] = live ? a.A_lo[at] : u32x4{0, 0, 0, 0};
         }
-    if (EPI != FEPI_RESID && EPI != FEPI_STORE && J == 1) {   // published by the first barrier
+    if (EPI != FEPI_RESID && EPI != FEPI_STORE && !SPLIT) {   // published by the first barrier
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
     }
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 #pragma unroll
             for (int ww = 0; ww < PW; ++ww) v += rb[ww * (MT * 256) + wave * 64 + lane];
             const int m = 16 * (wave >> 2) + 4 * (lane >> 4) + (wave & 3), c = lane & 15;
-            if (J > 1) {
+            if (SPLIT) {
                 a.partials[((size_t)j * a.part_rows + m) * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c] = v;
             } else if (TPU == 2 && part == 0) {
                 keep = v;
@@ -791,22 +792,42 @@ __host__ int small_kpw(int KT, int mt)
     return (KT % (PW * 7) == 0 && KT % (PW * 8) != 0) ? 7 : 8;
 }
 
+struct SmallPlan {
+    int mt, kpw, J, upw, groups;
+};
+
+__host__ SmallPlan small_plan(const FusedGemmArgs &a)
+{
+    SmallPlan p;
+    p.mt = a.M <= 16 ? 1 : 2;
+    p.kpw = small_kpw(a.KT, p.mt);
+    p.J = (a.KT + PW * p.kpw - 1) / (PW * p.kpw);
+    const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
+    int groups_target = n_cu / p.J;
+    if (groups_target < 1) groups_target = 1;
+    p.upw = (a.n_units + groups_target - 1) / groups_target;
+    p.groups = (a.n_units + p.upw - 1) / p.upw;
+    return p;
+}
+
 template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue, hipEvent_t t0, hipEvent_t t1)
 {
-    const int mt = a.M <= 16 ? 1 : 2;
-    const int kpw = small_kpw(a.KT, mt);
-    a.J = (a.KT + PW * kpw - 1) / (PW * kpw);
-    const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
-    int groups_target = n_cu / a.J;
-    if (groups_target < 1) groups_target = 1;
-    a.upw = (a.n_units + groups_target - 1) / groups_target;
-    const int groups = (a.n_units + a.upw - 1) / a.upw;
+    const SmallPlan sp = small_plan(a);
+    const int mt = sp.mt, kpw = sp.kpw, groups = sp.groups;
+    a.J = sp.J;
+    a.upw = sp.upw;
     a.part_rows = 16 * mt;
     if (a.J > 1 && (size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
     const dim3 grid(groups * a.J), block(PW * 64);
-    if (mt == 2) hipExtLaunchKernelGGL((pgemm_kernel<EPI, 4, 2>), grid, block, 0, s, t0, t1, 0, a);
-    else if (kpw == 7) hipExtLaunchKernelGGL((pgemm_kernel<EPI, 7, 1>), grid, block, 0, s, t0, t1, 0, a);
-    else hipExtLaunchKernelGGL((pgemm_kernel<EPI, 8, 1>), grid, block, 0, s, t0, t1, 0, a);
+#define SSSD_PLAUNCH(KPW, MT)                                                                                   \
+    do {                                                                                                        \
+        if (a.J > 1) hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, MT, true>), grid, block, 0, s, t0, t1, 0, a); \
+        else hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, MT, false>), grid, block, 0, s, t0, t1, 0, a);       \
+    } while (0)
+    if (mt == 2) SSSD_PLAUNCH(4, 2);
+    else if (kpw == 7) SSSD_PLAUNCH(7, 1);
+    else SSSD_PLAUNCH(8, 1);
+#undef SSSD_PLAUNCH
     *needs_epilogue = a.J > 1;
     return hipGetLastError();
 }
