@@ -19,10 +19,13 @@ struct LayerW {
 struct Buffers {
     float *X;
     uint16_t *Ah_hi, *Ah_lo, *Aq_hi, *Aq_lo, *Af_hi, *Af_lo;
+    uint16_t *Ah2_hi, *Ah2_lo;   // normed stream after the attention block (O writes, gate/up reads); Ah_*: after the MLP block
     uint16_t *Qp, *Qp_lo;
     float *part_o, *part_ml, *part_val;
     int *part_idx;
     int32_t *pos_base, *err_flag, *that_dbg, *rope_pos;
+    unsigned long long *chain_bar;   // barrier counters of the chained-GEMM launches (zeroed once, never reset)
+    int32_t *chain_err;
     uint32_t *anc;
     float *rope_cs, *ssq1;
     uint8_t *staging;
@@ -60,6 +63,8 @@ struct sssd_ctx {
     double prof_ms[SSSD_PROF_CLASSES];
     int64_t prof_n[SSSD_PROF_CLASSES];
     int device, n_cu;
+    int use_chain;                    // O/gate-up/down/next-QKV in one launch when the step allows
+    unsigned long long chain_epoch;   // barriers completed by those launches so far
 };
 
 namespace {
@@ -115,6 +120,8 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.X = (float *)take((size_t)S.m_alloc * D.h * 4);
     b.Ah_hi = (uint16_t *)take(S.tiles_alloc * KTh * 1024);
     b.Ah_lo = (uint16_t *)take(S.tiles_alloc * KTh * 1024);
+    b.Ah2_hi = (uint16_t *)take(S.tiles_alloc * KTh * 1024);
+    b.Ah2_lo = (uint16_t *)take(S.tiles_alloc * KTh * 1024);
     b.Aq_hi = (uint16_t *)take(S.tiles_alloc * KTq * 1024);
     b.Aq_lo = (uint16_t *)take(S.tiles_alloc * KTq * 1024);
     b.Af_hi = (uint16_t *)take(S.tiles_alloc * KTf * 1024);
@@ -135,6 +142,8 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.rope_pos = (int32_t *)take((size_t)S.m_alloc * 4);
     b.anc = (uint32_t *)take((size_t)S.m_alloc * 4);
     b.err_flag = (int32_t *)take(4);
+    b.chain_bar = (unsigned long long *)take(16 * 9 * sizeof(unsigned long long));
+    b.chain_err = (int32_t *)take(4);
     b.ssq1 = (float *)take((size_t)S.m_alloc * (D.h / 16) * 4);
     b.that_dbg = (int32_t *)take((size_t)S.m_alloc * 4);
     b.rope_cs = (float *)take((size_t)D.max_seq * (D.d / 2) * 2 * 4);
@@ -359,6 +368,8 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
         hipDeviceProp_t prop;
         INIT_TRY(hipGetDeviceProperties(&prop, c->device));
         c->n_cu = prop.multiProcessorCount;
+        c->use_chain = 0;   // measured no faster than the separate launches so far: opt-in (sssd_set_gemm_chain)
+        c->chain_epoch = 0;
     }
     INIT_TRY(hipStreamSynchronize(s));
     c->magic = MAGIC;
@@ -434,46 +445,79 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
         Prof p(c, s, SSSD_PROF_ELEM);
         return launch_stream_epilogue(f, epi, s);
     };
-    for (int l = 0; l < D.L; ++l) {
+    auto set_qkv = [&](FusedGemmArgs &g, int l) {
         const LayerW &lw = c->layers[l];
+        g.A_hi = (const u32x4 *)W.Ah_hi; g.A_lo = (const u32x4 *)W.Ah_lo; g.KT = KTh; g.ssq_in = W.ssq1;
+        g.W0 = (const u32x4 *)lw.wq; g.W1 = (const u32x4 *)lw.wk; g.W2 = (const u32x4 *)lw.wv;
+        g.NT = D.qd / 16;
+        g.Kc = c->Kc + (size_t)l * c->S.kv_layer_elems; g.Vc = c->Vc + (size_t)l * c->S.kv_layer_elems;
+        g.n_units = (D.nq + 2 * D.nkv) * (D.d / 32); g.Ntot = D.qd + 2 * D.kd;
+    };
+    auto set_o = [&](FusedGemmArgs &g, int l) {
+        const LayerW &lw = c->layers[l];
+        g.A_hi = (const u32x4 *)W.Aq_hi; g.A_lo = (const u32x4 *)W.Aq_lo; g.KT = KTq;
+        g.W0 = (const u32x4 *)lw.wo; g.NT = D.h / 16; g.gamma_next = lw.mlp_norm;
+        g.n_units = g.NT; g.Ntot = D.h;
+        g.out_hi = W.Ah2_hi; g.out_lo = W.Ah2_lo; g.ssq_out = W.ssq1;
+    };
+    auto set_gate_up = [&](FusedGemmArgs &g, int l) {
+        const LayerW &lw = c->layers[l];
+        g.A_hi = (const u32x4 *)W.Ah2_hi; g.A_lo = (const u32x4 *)W.Ah2_lo; g.KT = KTh; g.ssq_in = W.ssq1;
+        g.W0 = (const u32x4 *)lw.wg; g.W1 = (const u32x4 *)lw.wu;
+        g.NT = D.f / 16; g.n_units = g.NT; g.Ntot = 2 * D.f;
+        g.out_hi = W.Af_hi; g.out_lo = W.Af_lo; g.KT_out = KTf;
+    };
+    auto set_down = [&](FusedGemmArgs &g, int l) {
+        const LayerW &lw = c->layers[l];
+        g.A_hi = (const u32x4 *)W.Af_hi; g.A_lo = (const u32x4 *)W.Af_lo; g.KT = KTf;
+        g.W0 = (const u32x4 *)lw.wd; g.NT = D.h / 16;
+        g.n_units = g.NT; g.Ntot = D.h;
+        g.gamma_next = l + 1 < D.L ? c->layers[l + 1].attn_norm : c->final_norm;
+        g.out_hi = W.Ah_hi; g.out_lo = W.Ah_lo; g.ssq_out = W.ssq1;
+    };
+    auto set_lm = [&](FusedGemmArgs &g) {
+        g.A_hi = (const u32x4 *)W.Ah_hi; g.A_lo = (const u32x4 *)W.Ah_lo; g.KT = KTh; g.ssq_in = W.ssq1;
+        g.W0 = (const u32x4 *)c->lm_head; g.NT = D.V / 16;
+        g.n_units = g.NT; g.Ntot = D.V;
+    };
+    // Per layer: QKV, attention, then O, gate/up, down and the NEXT QKV (after the last layer: the LM
+    // head) -- those four in one launch when the step is small enough, else one by one.
+    set_qkv(f, 0);
+    HIP_TRY(fgemm(FEPI_QKV));
+    for (int l = 0; l < D.L; ++l) {
         uint16_t *Kl = c->Kc + (size_t)l * c->S.kv_layer_elems, *Vl = c->Vc + (size_t)l * c->S.kv_layer_elems;
-        // QKV
-        f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
-        f.W0 = (const u32x4 *)lw.wq; f.W1 = (const u32x4 *)lw.wk; f.W2 = (const u32x4 *)lw.wv;
-        f.NT = D.qd / 16; f.Kc = Kl; f.Vc = Vl;
-        f.n_units = (D.nq + 2 * D.nkv) * (D.d / 32); f.Ntot = D.qd + 2 * D.kd;
-        HIP_TRY(fgemm(FEPI_QKV));
         {
             AttnArgs a{W.Qp, W.Qp_lo, Kl, Vl, kv_geom(c), W.pos_base, W.anc, W.part_o, W.part_ml, W.Aq_hi, W.Aq_lo, B, k, 0, 0};
             Prof p(c, s, SSSD_PROF_ATTN);
             HIP_TRY(launch_attention(D, a, s));
         }
-        // O
-        f.A_hi = (const u32x4 *)W.Aq_hi; f.A_lo = (const u32x4 *)W.Aq_lo; f.KT = KTq;
-        f.W0 = (const u32x4 *)lw.wo; f.NT = D.h / 16; f.gamma_next = lw.mlp_norm;
-        f.n_units = f.NT; f.Ntot = D.h;
-        f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
-        HIP_TRY(fgemm(FEPI_RESID));
-        // gate/up
-        f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
-        f.W0 = (const u32x4 *)lw.wg; f.W1 = (const u32x4 *)lw.wu;
-        f.NT = D.f / 16; f.n_units = f.NT; f.Ntot = 2 * D.f;
-        f.out_hi = W.Af_hi; f.out_lo = W.Af_lo; f.KT_out = KTf;
-        HIP_TRY(fgemm(FEPI_SWIGLU));
-        // down
-        f.A_hi = (const u32x4 *)W.Af_hi; f.A_lo = (const u32x4 *)W.Af_lo; f.KT = KTf;
-        f.W0 = (const u32x4 *)lw.wd; f.NT = D.h / 16;
-        f.n_units = f.NT; f.Ntot = D.h;
-        f.gamma_next = l + 1 < D.L ? c->layers[l + 1].attn_norm : c->final_norm;
-        f.out_hi = W.Ah_hi; f.out_lo = W.Ah_lo; f.ssq_out = W.ssq1;
-        HIP_TRY(fgemm(FEPI_RESID));
+        const bool last = l + 1 == D.L;
+        const int last_epi = last ? FEPI_LM : FEPI_QKV;
+        FusedGemmArgs g[4];
+        g[0] = f; set_o(g[0], l);
+        g[1] = g[0]; set_gate_up(g[1], l);
+        g[2] = g[1]; set_down(g[2], l);
+        g[3] = g[2];
+        if (last) set_lm(g[3]);
+        else set_qkv(g[3], l + 1);
+        const bool chained = c->use_chain && stream_chain_supported(g, last_epi);
+        if (chained) {
+            Prof p(c, s, SSSD_PROF_GEMM, true);
+            HIP_TRY(launch_stream_chain(g, last_epi, W.chain_bar, &c->chain_epoch, W.chain_err, s, p.start(), p.stop()));
+        }
+        if (!chained) {
+            f = g[0]; HIP_TRY(fgemm(FEPI_RESID));
+            f = g[1]; HIP_TRY(fgemm(FEPI_SWIGLU));
+            f = g[2]; HIP_TRY(fgemm(FEPI_RESID));
+            if (last && c->dbg_hidden)
+                HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
+            f = g[3]; HIP_TRY(fgemm(last_epi));
+        } else {
+            f = g[3];
+            if (last && c->dbg_hidden)   // the LM head leaves the stream as the last down projection wrote it
+                HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
+        }
     }
-    if (c->dbg_hidden)
-        HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
-    f.A_hi = (const u32x4 *)W.Ah_hi; f.A_lo = (const u32x4 *)W.Ah_lo; f.KT = KTh; f.ssq_in = W.ssq1;
-    f.W0 = (const u32x4 *)c->lm_head; f.NT = D.V / 16;
-    f.n_units = f.NT; f.Ntot = D.V;
-    HIP_TRY(fgemm(FEPI_LM));
     if (smp) {
         if (c->dbg_logits)
             HIP_TRY(hipMemcpyAsync(c->dbg_logits, smp->logits, (size_t)M * D.V * 4, hipMemcpyDeviceToDevice, s));
@@ -556,13 +600,28 @@ int sssd_kv_rollback(sssd_ctx *c, int32_t B, int32_t *lens, const int32_t *accep
     return SSSD_OK;
 }
 
+int sssd_set_gemm_chain(sssd_ctx *c, int32_t enable)
+{
+    if (!valid(c)) return SSSD_EINVAL;
+    c->use_chain = enable != 0;
+    return SSSD_OK;
+}
+
 int sssd_verify_sync(sssd_ctx *c, void *stream)
 {
     if (!valid(c)) return SSSD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     int32_t flag = 0;
+    int32_t chain_flag = 0;
     HIP_TRY(hipMemcpyAsync(&flag, c->W.err_flag, 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(&chain_flag, c->W.chain_err, 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if (chain_flag) {   // a grid barrier of a chained launch gave up: that step's results are void
+        HIP_TRY(hipMemsetAsync(c->W.chain_err, 0, 4, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        c->use_chain = 0;   // the counters no longer match the epoch: separate launches from here on
+        return SSSD_EHIP;
+    }
     if (flag) {
         HIP_TRY(hipMemsetAsync(c->W.err_flag, 0, 4, s));
         HIP_TRY(hipStreamSynchronize(s));

@@ -56,6 +56,7 @@ struct FusedGemmArgs {
     size_t partial_bytes;
     int seg0, seg1;               // tiles of W0 and of W1 in the concatenated output (M > 16 kernel)
     int upw, J, part_rows, kps;   // filled in by the launcher: units per workgroup, K slices, rows per slice, k-tiles per slice
+    int groups;                   // ... and column groups (M <= 32: the grid is groups * J workgroups)
 };
 // M <= stream_gemm_max_rows(): persistent weight streamer; NT must be the tile count of W0.
 int stream_gemm_max_rows();
@@ -68,6 +69,13 @@ size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-lev
 hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,
                               hipEvent_t t1);
 hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s);
+// O, gate/up, down and then `last_epilogue` (FEPI_QKV of the next layer, or FEPI_LM) in one launch:
+// possible when M <= 16 and only the down projection needs a split K (stream_chain_supported).
+// bar: 16 * 9 zero-initialised 64-bit counters that only these launches touch; *epoch: running
+// barrier count, kept by the caller next to them; err: set if a barrier wait gave up.
+bool stream_chain_supported(const FusedGemmArgs (&g)[4], int last_epilogue);
+hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigned long long *bar, unsigned long long *epoch,
+                               int *err, hipStream_t s, hipEvent_t t0, hipEvent_t t1);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const KvGeom &kv, const uint16_t *embed, const uint16_t *gamma,
                               float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos,
                               uint32_t *anc, int32_t *err_flag, hipStream_t s);

@@ -1,0 +1,44 @@
+"""The optional chained launch (O, gate/up, down and the next QKV / the LM head in one launch with
+grid-wide barriers): same arithmetic in the same order, so every output must be bit-identical to
+the separate launches, and it must meet the oracle like they do."""
+import pytest
+import torch
+
+from harness import Pair, compare_step, compare_tree_step, step_tree
+from sssd_synth import MODEL_SHAPES, uniform_int
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def test_tiny_chain_matches_separate_launches_and_oracle():
+    """Tiny shape (no GEMM splits K): chained steps of several sizes, a tree step, and a step too
+    large for the chained launch (17 rows: it must fall back without a trace)."""
+    s = MODEL_SHAPES["tiny"]
+    B, k = 2, 7
+    a = Pair(s, seed=71, max_batch=B, max_k=k + 1, max_seq=200, unit_gains=False)
+    b = Pair(s, seed=71, max_batch=B, max_k=k + 1, max_seq=200, unit_gains=False)
+    b.ctx.sssd_set_gemm_chain(True)
+    ctxs = [33, 90]
+    for p in (a, b):
+        for i in range(B):
+            p.prefill_random_kv(72, i, ctxs[i], oracle_slot=i if p is a else None)
+    lens = torch.tensor(ctxs, dtype=torch.int32)
+    for step, kk in enumerate([7, 0, 3, 7, 8]):            # 8: M = 18 rows, not chained
+        tokens = uniform_int(73, step, (B, kk + 1), 0, s.vocab - 1)
+        ra, rb = a.step(tokens, lens), b.step(tokens, lens)
+        assert torch.equal(ra["logits"], rb["logits"]) and torch.equal(ra["hidden"], rb["hidden"])
+        assert torch.equal(ra["accepted_len"], rb["accepted_len"]) and torch.equal(ra["next_token"], rb["next_token"])
+        if step == 0:
+            e, ex, r = compare_step(rb, a.oracle.verify_step(tokens, lens), tokens)
+            say(f"chain tiny: logit err vs oracle {e:.2e}, exempt {ex}/{r}")
+    raw = uniform_int(74, 1, (B, k + 1), 0, 1 << 20).tolist()
+    parents = torch.tensor([[0] + [raw[i][j] % j for j in range(1, k + 1)] for i in range(B)], dtype=torch.int32)
+    tokens = uniform_int(74, 2, (B, k + 1), 0, s.vocab - 1)
+    ta, tb = step_tree(a, tokens, parents, lens), step_tree(b, tokens, parents, lens)
+    assert torch.equal(ta["logits"], tb["logits"]) and torch.equal(ta["path"], tb["path"])
+    e, ex, r = compare_tree_step(tb, a.oracle.verify_step_tree(tokens, parents, lens, compact=False), tokens, parents)
+    say(f"chain tiny tree: logit err vs oracle {e:.2e}, exempt {ex}/{r}")
