@@ -958,7 +958,7 @@ struct QPlan {
 
 // Column groups and the K split.  A workgroup slot is what one compute unit can hold of this kernel
 // at once (by the registers the row count needs, for 1..5 row tiles of 32: 2, 2, 2, 1, 1 workgroups
-// of eight waves, 5, 3, 2, 2, 2 of four); the split is the smallest J whose groups*J workgroups fill whole rounds of slots to at
+// of eight waves, 5, 3, 2, 2, 2 of four; one per compute unit for the small matrices below 129 rows); the split is the smallest J whose groups*J workgroups fill whole rounds of slots to at
 // least 85 % (else the best-filling one), with at least 8 k-tiles per slice and at most 16 slices.
 __host__ QPlan q_plan(int Ntot, int K, int M)
 {
@@ -967,7 +967,9 @@ __host__ QPlan q_plan(int Ntot, int K, int M)
     static const int resident8[6] = {0, 2, 2, 2, 1, 1}, resident4[6] = {0, 5, 3, 2, 2, 2};
     QPlan p;
     p.qw = (size_t)Ntot * (size_t)K * 2 < ((size_t)64 << 20) ? 4 : 8;
-    const int slots = 256 * (p.qw == 8 ? resident8[mt32] : resident4[mt32]);
+    // The small matrices at up to 128 rows run best with about one workgroup per compute unit: more
+    // slices only add partial-sum traffic, which there is a sizeable fraction of the weight bytes.
+    const int slots = (p.qw == 4 && mt32 <= 4) ? 256 : 256 * (p.qw == 8 ? resident8[mt32] : resident4[mt32]);
     p.groups = (NT32 + p.qw * QNG - 1) / (p.qw * QNG);
     int jmax = KT / 8;
     if (jmax > 16) jmax = 16;
