@@ -1119,8 +1119,9 @@ hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigne
     if (sp[2].kpw == 7) { if (split) SSSD_CLAUNCH(7, true); else SSSD_CLAUNCH(7, false); }
     else { if (split) SSSD_CLAUNCH(8, true); else SSSD_CLAUNCH(8, false); }
 #undef SSSD_CLAUNCH
-    *epoch += 3 + (split ? 1 : 0);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) *epoch += 3 + (split ? 1 : 0);   // a launch that did not happen passed no barrier
+    return e;
 }
 
 // Split-K scratch needed for M rows: the largest J * rows * Ntot over the model's GEMMs.
