@@ -430,9 +430,8 @@ struct ChainArgs {
     unsigned long long *bar;     // [0]: groups that arrived; [16*(1+i)]: arrivals of group i (of up to 8), never reset
     unsigned long long epoch;    // barriers completed by all earlier launches
     int *err;                    // set when a barrier wait gave up
+    int spin_limit;              // polls of the top counter before a wait gives up
 };
-
-constexpr int CHAIN_SPIN_LIMIT = 1 << 20;
 
 // Boundary number `index` (0-based) between two GEMMs of this launch: a grid-wide barrier with the
 // next GEMM's first weight loads (preload()) issued around it.  Memory operations of a wave retire
@@ -461,7 +460,7 @@ __device__ __forceinline__ bool chain_boundary(const ChainArgs &c, int index, in
     if (threadIdx.x == 0) {
         int ok = 1, spins = 0;
         while (__hip_atomic_load(c.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < t * G) {
-            if (++spins > CHAIN_SPIN_LIMIT) {
+            if (++spins > c.spin_limit) {
                 ok = 0;
                 *c.err = 1;
                 break;
@@ -1090,7 +1089,7 @@ bool stream_chain_supported(const FusedGemmArgs (&g)[4], int last_epilogue)
 }
 
 hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigned long long *bar, unsigned long long *epoch,
-                               int *err, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
+                               int *err, int spin_limit, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
 {
     if (!stream_chain_supported(g, last_epilogue)) return hipErrorInvalidValue;
     for (int i = 0; i < 4; ++i)
@@ -1108,7 +1107,7 @@ hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigne
         g[i].J = sp[i].J; g[i].upw = sp[i].upw; g[i].groups = sp[i].groups; g[i].part_rows = 16;
         c.g[i] = g[i];
     }
-    c.bar = bar; c.epoch = *epoch; c.err = err;
+    c.bar = bar; c.epoch = *epoch; c.err = err; c.spin_limit = spin_limit > 0 ? spin_limit : 1;
     const bool split = sp[2].J > 1, lm = last_epilogue == FEPI_LM;
     const dim3 grid(n_cu), block(PW * 64);   // one workgroup per compute unit: all resident, as the barriers need
 #define SSSD_CLAUNCH(KPW, SPLIT)                                                                                   \

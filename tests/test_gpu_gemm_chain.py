@@ -42,3 +42,38 @@ def test_tiny_chain_matches_separate_launches_and_oracle():
     assert torch.equal(ta["logits"], tb["logits"]) and torch.equal(ta["path"], tb["path"])
     e, ex, r = compare_tree_step(tb, a.oracle.verify_step_tree(tokens, parents, lens, compact=False), tokens, parents)
     say(f"chain tiny tree: logit err vs oracle {e:.2e}, exempt {ex}/{r}")
+
+
+def test_barrier_give_up_is_reported_and_the_context_recovers():
+    """The error path, forced from the host: with a barrier count no launch can reach and a limit of
+    8 polls every workgroup of the chained launches leaves through the give-up branch (the kernels
+    end normally).  The sync call must say so once; the context then runs separate launches, and the
+    chain again when asked to, both bit-identical to a context that never failed."""
+    s = MODEL_SHAPES["tiny"]
+    B, k = 2, 5
+    a = Pair(s, seed=81, max_batch=B, max_k=k, max_seq=120, unit_gains=False)
+    b = Pair(s, seed=81, max_batch=B, max_k=k, max_seq=120, unit_gains=False)
+    ctxs = [17, 64]
+    for p in (a, b):
+        for i in range(B):
+            p.prefill_random_kv(82, i, ctxs[i])
+    lens = torch.tensor(ctxs, dtype=torch.int32)
+    tokens = uniform_int(83, 1, (B, k + 1), 0, s.vocab - 1)
+    ref = a.step(tokens, lens)
+    b.ctx.sssd_set_gemm_chain(True)
+    b.ctx.sssd_debug_chain_wait(8, 1000)
+    dev = b.dev
+    t, ln = tokens.to(dev, torch.int32), lens.to(dev, torch.int32)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    b.ctx.sssd_verify_step(t, ln, acc, nxt)
+    rc = b.ctx.sssd_verify_sync()
+    assert rc == -4, rc                                   # SSSD_EHIP
+    assert b.ctx.sssd_verify_sync() == 0                  # reported once
+    got = b.step(tokens, lens)                            # separate launches now
+    assert torch.equal(ref["logits"], got["logits"]) and torch.equal(ref["next_token"], got["next_token"])
+    b.ctx.sssd_set_gemm_chain(True)                       # counters and epoch were started over
+    for _ in range(2):
+        got = b.step(tokens, lens)
+        assert torch.equal(ref["logits"], got["logits"]) and torch.equal(ref["accepted_len"], got["accepted_len"])
+    say("chain give-up: reported as SSSD_EHIP once, separate launches and the re-enabled chain bit-identical")
