@@ -26,6 +26,7 @@ struct Buffers {
     int32_t *pos_base, *err_flag, *that_dbg, *rope_pos;
     unsigned long long *chain_bar;   // barrier counters of the chained-GEMM launches (zeroed once, never reset)
     int32_t *chain_err;
+    int *tail_count;   // TAIL_SLOTS split-K arrival counters, zero between launches
     uint32_t *anc;
     float *rope_cs, *ssq1;
     uint8_t *staging;
@@ -103,6 +104,8 @@ Dims make_dims(const sssd_model_config *c)
 }
 
 // Lays the workspace out; with base == nullptr it only measures.
+constexpr int TAIL_SLOTS = 256;
+
 size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
 {
     size_t off = 0;
@@ -145,6 +148,7 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.err_flag = (int32_t *)take(4);
     b.chain_bar = (unsigned long long *)take(16 * 9 * sizeof(unsigned long long));
     b.chain_err = (int32_t *)take(4);
+    b.tail_count = (int *)take(TAIL_SLOTS * sizeof(int));
     b.ssq1 = (float *)take((size_t)S.m_alloc * (D.h / 16) * 4);
     b.that_dbg = (int32_t *)take((size_t)S.m_alloc * 4);
     b.rope_cs = (float *)take((size_t)D.max_seq * (D.d / 2) * 2 * 4);
@@ -439,6 +443,7 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
     f.n_cu = c->n_cu; f.partials = W.partials; f.partial_bytes = W.partial_bytes;
     auto fgemm = [&](int epi) -> hipError_t {
         bool more = false;
+        f.tail_count = W.tail_count; f.tail_slots = TAIL_SLOTS;   // the launcher clears it when it does not apply
         {
             Prof p(c, s, SSSD_PROF_GEMM, true);
             hipError_t e = launch_stream_gemm(f, epi, s, &more, p.start(), p.stop());

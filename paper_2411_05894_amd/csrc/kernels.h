@@ -54,6 +54,8 @@ struct FusedGemmArgs {
     float *out;                   // STORE: [M][Ntot] fp32
     float *partials;              // split-K scratch [J][part_rows][Ntot] fp32
     size_t partial_bytes;
+    int *tail_count;              // M <= 32 with a split K: tail_slots arrival counters, zero between launches; with them
+    int tail_slots;               // the last workgroup of a column group sums the slices itself (null: epilogue launch)
     int seg0, seg1;               // tiles of W0 and of W1 in the concatenated output (M > 16 kernel)
     int upw, J, part_rows, kps;   // filled in by the launcher: units per workgroup, K slices, rows per slice, k-tiles per slice
     int groups;                   // ... and column groups (M <= 32: the grid is groups * J workgroups)

@@ -193,114 +193,6 @@ template <bool COH = false> __device__ __forceinline__ float row_rstd(const Fuse
     return rsqrtf(sum / (float)a.h + a.eps);
 }
 
-// ------------------------------------------------------------------ M <= 32 ----
-constexpr int PW = 16;  // waves per workgroup
-
-template <int KPW, int MT, bool PREFETCH, int WN>
-__device__ __forceinline__ void stream_tile(const u32x4 (&ah)[MT][KPW], const u32x4 (&al)[MT][KPW], u32x4 (&w)[WN], const u32x4 *wn,
-                                            const int (&koff)[KPW], f32x4 (&acc)[MT])
-{
-    f32x4 s0[MT], s1[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) s0[mt] = s1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            s0[mt] = mfma(ah[mt][i], w[i], s0[mt]);
-            s1[mt] = mfma(al[mt][i], w[i], s1[mt]);
-        }
-        if (PREFETCH) w[i] = __builtin_nontemporal_load(wn + koff[i]);
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = s0[mt] + s1[mt];
-}
-
-// grid = n_groups * J workgroups of 1024 threads; MT row tiles of 16 (M <= 16*MT).  Workgroup
-// (grp, j) computes units [grp*upw, (grp+1)*upw) over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1
-// (SPLIT) it stores fp32 partial tiles for epi_kernel instead of applying the epilogue, and the
-// unsplit instantiation carries none of that code (the QKV kernel is at the register limit).
-template <int EPI, int KPW, int MT, bool SPLIT>
-__global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
-{
-    constexpr int TPU = Unit<EPI>::TILES;
-    constexpr int NBUF = MT == 1 ? 2 : 1;   // two row tiles: one reduction buffer (32 KiB) and a second barrier
-    __shared__ float red[NBUF][PW][MT * 256];
-    __shared__ float rstd_s[MT * 16];
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int J = SPLIT ? a.J : 1, j = SPLIT ? blockIdx.x % J : 0, grp = SPLIT ? blockIdx.x / J : blockIdx.x;
-    const int KT = a.KT;
-    const int kt0 = (j * PW + wave) * KPW;
-    // Units grp, grp + groups, grp + 2*groups, ... so that at any time the workgroups of a launch
-    // read neighbouring tiles (measured 3 % faster on the layer matrices); the LM head, 30 times as
-    // many tiles, measured 3 % faster with a contiguous run of upw units per workgroup.
-    const int groups = gridDim.x / J;
-    constexpr bool RUNS = EPI == FEPI_LM;
-    const int u_begin = RUNS ? grp * a.upw : grp, u_stride = RUNS ? 1 : groups;
-    if (u_begin >= a.n_units) return;
-    const int n_mine = RUNS ? (u_begin + a.upw < a.n_units ? a.upw : a.n_units - u_begin) : (a.n_units - grp + groups - 1) / groups;
-    const int n_steps = n_mine * TPU;
-
-    // k-tiles past the matrix (ragged K split) contribute zero activations and re-read the last tile.
-    int koff[KPW];
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) koff[i] = (kt0 + i < KT ? kt0 + i : KT - 1) * 64;
-
-    u32x4 w[KPW], ah[MT][KPW], al[MT][KPW];
-    const u32x4 *wp = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin, 0)) + lane;
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) w[i] = __builtin_nontemporal_load(wp + koff[i]);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int i = 0; i < KPW; ++i) {
-            const bool live = kt0 + i < KT;
-            const size_t at = (size_t)mt * KT * 64 + koff[i] + lane;
-            ah[mt][i] = live ? a.A_hi[at] : u32x4{0, 0, 0, 0};
-            al[mt][i] = live ? a.A_lo[at] : u32x4{0, 0, 0, 0};
-        }
-    if (EPI != FEPI_RESID && EPI != FEPI_STORE && !SPLIT) {   // published by the first barrier
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
-    }
-
-    float keep = 0.f;
-    for (int s = 0; s < n_steps; ++s) {
-        const int unit = u_begin + (s / TPU) * u_stride, part = s % TPU;
-        f32x4 acc[MT];
-        if (s + 1 < n_steps) {
-            const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + ((s + 1) / TPU) * u_stride, (s + 1) % TPU)) + lane;
-            stream_tile<KPW, MT, true, KPW>(ah, al, w, wn, koff, acc);
-        } else {
-            stream_tile<KPW, MT, false, KPW>(ah, al, w, nullptr, koff, acc);
-        }
-        float *rb = &red[NBUF == 2 ? (s & 1) : 0][0][0];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) rb[wave * (MT * 256) + mt * 256 + r * 64 + lane] = acc[mt][r];
-        __syncthreads();
-        // Two buffers: buffer s&1 is rewritten at step s+2, after the barrier of step s+1, which the
-        // reducing waves reach only after they have read it.  One buffer: the barrier below.
-        if (wave < 4 * MT) {
-            float v = 0.f;
-#pragma unroll
-            for (int ww = 0; ww < PW; ++ww) v += rb[ww * (MT * 256) + wave * 64 + lane];
-            const int m = 16 * (wave >> 2) + 4 * (lane >> 4) + (wave & 3), c = lane & 15;
-            if (SPLIT) {
-                a.partials[((size_t)j * a.part_rows + m) * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c] = v;
-            } else if (TPU == 2 && part == 0) {
-                keep = v;
-            } else {
-                const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[m];
-                if (TPU == 2) epilogue<EPI>(a, unit, m, c, m < a.M, keep, v, rs);
-                else epilogue<EPI>(a, unit, m, c, m < a.M, v, 0.f, rs);
-            }
-        }
-        if (NBUF == 1) __syncthreads();
-    }
-}
-
 // ---- eight columns per thread ----
 struct Vec8 {
     float v[8];
@@ -407,6 +299,169 @@ template <bool COH> __device__ __forceinline__ void resid_block(const FusedGemmA
     }
     ss += __shfl_xor(ss, 16);   // the other 8 columns of the 16-column group
     if (live && !(kg & 1)) st<COH>(a.ssq_out + (size_t)m * (a.h >> 4) + (col >> 4), ss);
+}
+
+// ------------------------------------------------------------------ M <= 32 ----
+constexpr int PW = 16;  // waves per workgroup
+
+template <int KPW, int MT, bool PREFETCH, int WN>
+__device__ __forceinline__ void stream_tile(const u32x4 (&ah)[MT][KPW], const u32x4 (&al)[MT][KPW], u32x4 (&w)[WN], const u32x4 *wn,
+                                            const int (&koff)[KPW], f32x4 (&acc)[MT])
+{
+    f32x4 s0[MT], s1[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) s0[mt] = s1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            s0[mt] = mfma(ah[mt][i], w[i], s0[mt]);
+            s1[mt] = mfma(al[mt][i], w[i], s1[mt]);
+        }
+        if (PREFETCH) w[i] = __builtin_nontemporal_load(wn + koff[i]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = s0[mt] + s1[mt];
+}
+
+// grid = n_groups * J workgroups of 1024 threads; MT row tiles of 16 (M <= 16*MT).  Workgroup
+// (grp, j) computes units [grp*upw, (grp+1)*upw) over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1
+// (SPLIT) it stores fp32 partial tiles for epi_kernel instead of applying the epilogue, and the
+// unsplit instantiation carries none of that code (the QKV kernel is at the register limit).
+template <int EPI, int KPW, int MT, bool SPLIT>
+__global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
+{
+    constexpr int TPU = Unit<EPI>::TILES;
+    constexpr int NBUF = MT == 1 ? 2 : 1;   // two row tiles: one reduction buffer (32 KiB) and a second barrier
+    __shared__ float red[NBUF][PW][MT * 256];
+    __shared__ float rstd_s[MT * 16];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int J = SPLIT ? a.J : 1, j = SPLIT ? blockIdx.x % J : 0, grp = SPLIT ? blockIdx.x / J : blockIdx.x;
+    const int KT = a.KT;
+    const int kt0 = (j * PW + wave) * KPW;
+    // Units grp, grp + groups, grp + 2*groups, ... so that at any time the workgroups of a launch
+    // read neighbouring tiles (measured 3 % faster on the layer matrices); the LM head, 30 times as
+    // many tiles, measured 3 % faster with a contiguous run of upw units per workgroup.
+    const int groups = gridDim.x / J;
+    constexpr bool RUNS = EPI == FEPI_LM;
+    const int u_begin = RUNS ? grp * a.upw : grp, u_stride = RUNS ? 1 : groups;
+    if (u_begin >= a.n_units) return;
+    const int n_mine = RUNS ? (u_begin + a.upw < a.n_units ? a.upw : a.n_units - u_begin) : (a.n_units - grp + groups - 1) / groups;
+    const int n_steps = n_mine * TPU;
+
+    // k-tiles past the matrix (ragged K split) contribute zero activations and re-read the last tile.
+    int koff[KPW];
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) koff[i] = (kt0 + i < KT ? kt0 + i : KT - 1) * 64;
+
+    u32x4 w[KPW], ah[MT][KPW], al[MT][KPW];
+    const u32x4 *wp = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin, 0)) + lane;
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) w[i] = __builtin_nontemporal_load(wp + koff[i]);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < KPW; ++i) {
+            const bool live = kt0 + i < KT;
+            const size_t at = (size_t)mt * KT * 64 + koff[i] + lane;
+            ah[mt][i] = live ? a.A_hi[at] : u32x4{0, 0, 0, 0};
+            al[mt][i] = live ? a.A_lo[at] : u32x4{0, 0, 0, 0};
+        }
+    if (EPI != FEPI_RESID && EPI != FEPI_STORE && !SPLIT) {   // published by the first barrier
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
+    }
+
+    float keep = 0.f;
+    for (int s = 0; s < n_steps; ++s) {
+        const int unit = u_begin + (s / TPU) * u_stride, part = s % TPU;
+        f32x4 acc[MT];
+        if (s + 1 < n_steps) {
+            const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + ((s + 1) / TPU) * u_stride, (s + 1) % TPU)) + lane;
+            stream_tile<KPW, MT, true, KPW>(ah, al, w, wn, koff, acc);
+        } else {
+            stream_tile<KPW, MT, false, KPW>(ah, al, w, nullptr, koff, acc);
+        }
+        float *rb = &red[NBUF == 2 ? (s & 1) : 0][0][0];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) rb[wave * (MT * 256) + mt * 256 + r * 64 + lane] = acc[mt][r];
+        __syncthreads();
+        // Two buffers: buffer s&1 is rewritten at step s+2, after the barrier of step s+1, which the
+        // reducing waves reach only after they have read it.  One buffer: the barrier below.
+        if (wave < 4 * MT) {
+            float v = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < PW; ++ww) v += rb[ww * (MT * 256) + wave * 64 + lane];
+            const int m = 16 * (wave >> 2) + 4 * (lane >> 4) + (wave & 3), c = lane & 15;
+            if (SPLIT) {
+                // device-scope: read back by the last workgroup of the group, on whichever die it runs
+                st<true>(a.partials + ((size_t)j * a.part_rows + m) * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c, v);
+            } else if (TPU == 2 && part == 0) {
+                keep = v;
+            } else {
+                const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[m];
+                if (TPU == 2) epilogue<EPI>(a, unit, m, c, m < a.M, keep, v, rs);
+                else epilogue<EPI>(a, unit, m, c, m < a.M, v, 0.f, rs);
+            }
+        }
+        if (NBUF == 1) __syncthreads();
+    }
+
+    // Split K with arrival counters: the workgroup of a column group that finishes last sums the
+    // group's slices (in slice order, so the result does not depend on which one that is) and applies
+    // the epilogue -- no second launch.  The slices were stored device-scope and each wave waits for
+    // its stores before the workgroup is counted; they are read back device-scope.  The counter is
+    // back at zero for the next launch on the stream.
+    if (SPLIT && a.tail_count) {
+        __shared__ int last_s;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int old = __hip_atomic_fetch_add(a.tail_count + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last_s = old == J - 1;
+            if (old == J - 1) __hip_atomic_store(a.tail_count + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!last_s) return;
+        constexpr bool SCALED = EPI != FEPI_RESID && EPI != FEPI_STORE;
+        if (SCALED) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
+            __syncthreads();
+        }
+        if (EPI == FEPI_RESID) {
+            // thread for thread what epi_kernel does (same order of every sum): a wave takes two units,
+            // 8 columns per thread, lanes 16 apart share a unit's sum of squares
+            const int r = lane & 15, kg = lane >> 4;
+            for (int i = 2 * wave + (kg >> 1); i - (kg >> 1) < n_mine; i += 2 * PW) {
+                const int unit = u_begin + i * u_stride, col = unit * 16 + (kg & 1) * 8;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = mt * 16 + r;
+                    const bool live = i < n_mine && m < a.M;
+                    Vec8 v0{};
+                    if (live) v0 = sum_slices<true>(a, m, col);
+                    resid_block<false>(a, m, col, live, kg, v0);
+                }
+            }
+        } else {
+            const size_t jstride = (size_t)a.part_rows * a.Ntot;
+            for (int e = threadIdx.x; e < n_mine * (MT * 256); e += PW * 64) {   // 16 adjacent lanes: one row of a unit
+                const int unit = u_begin + (e / (MT * 256)) * u_stride, m = (e % (MT * 256)) >> 4, c = e & 15;
+                float v[TPU];
+#pragma unroll
+                for (int part = 0; part < TPU; ++part) {
+                    const float *pp = a.partials + (size_t)m * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c;
+                    float sum = ld<true>(pp);
+                    for (int jj = 1; jj < J; ++jj) sum += ld<true>(pp + jj * jstride);
+                    v[part] = sum;
+                }
+                epilogue<EPI>(a, unit, m, c, m < a.M, v[0], TPU == 2 ? v[TPU - 1] : 0.f, SCALED ? rstd_s[m] : 1.f);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------- chained GEMMs, M <= 16 ----
@@ -1059,6 +1114,7 @@ template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool
     a.part_rows = 16 * mt;
     if (a.J > 1 && (size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
     const dim3 grid(groups * a.J), block(PW * 64);
+    if (groups > a.tail_slots) a.tail_count = nullptr;   // no counter for every group: epilogue launch
 #define SSSD_PLAUNCH(KPW, MT)                                                                                   \
     do {                                                                                                        \
         if (a.J > 1) hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, MT, true>), grid, block, 0, s, t0, t1, 0, a); \
@@ -1068,7 +1124,7 @@ template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool
     else if (kpw == 7) SSSD_PLAUNCH(7, 1);
     else SSSD_PLAUNCH(8, 1);
 #undef SSSD_PLAUNCH
-    *needs_epilogue = a.J > 1;
+    *needs_epilogue = a.J > 1 && !a.tail_count;
     return hipGetLastError();
 }
 
