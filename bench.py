@@ -23,7 +23,7 @@ PEAK_HBM_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each
 # calibrated against a 1 GiB copy kernel); source: profiles/verify_step_8b_b1_ctx2048_k8_hbm_traffic.md.
 # Only the workload those runs covered has a figure.
-MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "pgemm_kernel"): 120.03e6}
+MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "pgemm_kernel"): 120.50e6}
 
 WORKLOADS = {
     # name: (shape, B, ctx spec, k, k sweep)
