@@ -141,6 +141,33 @@ def test_8b_shape_chain_is_bit_identical(pair_8b):
 
 
 @pytest.mark.timeout(300)
+def test_8b_shape_split_k_sums_repeat_bit_for_bit(pair_8b):
+    """Steps whose GEMMs split K over workgroups (k=8: the down projection; k=16: every GEMM) hand the
+    slices from one workgroup to another inside a launch.  200 repetitions of the same step must give
+    the same logits bit for bit: a slice read before it was complete would show up as a difference."""
+    p, s = pair_8b, pair_8b.shape
+    p.prefill_random_kv(4, 0, 2048)
+    lens = torch.tensor([2048], dtype=torch.int32)
+    for k in (8, 16):
+        tokens = uniform_int(76, 1 + k, (1, k + 1), 0, s.vocab - 1)
+        t = tokens.to(p.dev, torch.int32).contiguous()
+        ln = lens.to(p.dev, torch.int32)
+        acc = torch.empty(1, dtype=torch.int32, device=p.dev)
+        nxt = torch.empty(1, dtype=torch.int32, device=p.dev)
+        first, bad = None, 0
+        for rep in range(200):
+            p.ctx.sssd_verify_step(t, ln, acc, nxt)
+            cur = p.logits[: k + 1]
+            if first is None:
+                first = cur.clone()
+            else:
+                bad += int(not torch.equal(first, cur))
+        assert p.ctx.sssd_verify_sync() == 0
+        assert bad == 0, (k, bad)
+        progress(f"split-K repeat k={k}: 200 steps, logits identical every time")
+
+
+@pytest.mark.timeout(300)
 def test_cfg3_8b_b32_ragged_k4(pair_8b):
     """Config 3: B=32, context lengths uniform in [1024, 4096], k=4.  Sequences 5 and 31 are
     recomputed by the oracle."""
