@@ -874,7 +874,8 @@ __device__ __forceinline__ int half_record(int lane, int hh) { return (lane & 15
 // activations; writes partials[j][row][col].  One 32-column tile per wave, so two or more waves
 // share a SIMD and cover each other's LDS and barrier waits; QW = 8 (256 columns per workgroup)
 // for the large matrices, QW = 4 for the small ones, whose K then splits half as often (measured:
-// 8 waves 15 % faster on gate/up and down at M = 160, 4 waves 10-15 % faster on QKV and O).
+// 8 waves 15 % faster on gate/up and down at M = 160, 4 waves 10-15 % faster on QKV and O, and on
+// every matrix at up to 64 rows).
 template <int MT32, int QW>
 __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_base, int NT16)
 {
@@ -1020,7 +1021,9 @@ __host__ QPlan q_plan(int Ntot, int K, int M)
     const int mt32 = M >= 160 ? 5 : (M + 31) / 32;
     static const int resident8[6] = {0, 2, 2, 2, 1, 1}, resident4[6] = {0, 5, 3, 2, 2, 2};
     QPlan p;
-    p.qw = (size_t)Ntot * (size_t)K * 2 < ((size_t)64 << 20) ? 4 : 8;
+    // four waves: the small matrices, and every matrix at up to 64 rows (measured at 36 and 64 rows: gate/up 59 -> 48
+    // and 64 -> 51 us, down 34 -> 32 and 37 -> 33 us; from 65 rows on eight waves win on the large matrices)
+    p.qw = ((size_t)Ntot * (size_t)K * 2 < ((size_t)64 << 20) || mt32 <= 2) ? 4 : 8;
     // The small matrices at up to 128 rows run best with about one workgroup per compute unit: more
     // slices only add partial-sum traffic, which there is a sizeable fraction of the weight bytes.
     const int slots = (p.qw == 4 && mt32 <= 4) ? 256 : 256 * (p.qw == 8 ? resident8[mt32] : resident4[mt32]);
