@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from harness import Pair, compare_step, compare_tree_step, step_tree
+from paper_2411_05894_amd import binding as sv
 from sssd_synth import MODEL_SHAPES, uniform_int
 
 pytestmark = pytest.mark.gpu
@@ -77,3 +78,37 @@ def test_barrier_give_up_is_reported_and_the_context_recovers():
         got = b.step(tokens, lens)
         assert torch.equal(ref["logits"], got["logits"]) and torch.equal(ref["accepted_len"], got["accepted_len"])
     say("chain give-up: reported as SSSD_EHIP once, separate launches and the re-enabled chain bit-identical")
+
+
+def test_chain_writes_the_paged_cache_like_the_separate_launches():
+    """The chained launch's last phase is the next layer's QKV projection, whose epilogue appends K/V
+    through the block table: with a shuffled table the step and the cache rows it leaves behind (read
+    back through the table) must equal those of separate launches on the same table."""
+    s = MODEL_SHAPES["tiny"]
+    B, k = 3, 4
+    a = Pair(s, seed=91, max_batch=B, max_k=k, max_seq=130, unit_gains=False)
+    b = Pair(s, seed=91, max_batch=B, max_k=k, max_seq=130, unit_gains=False)
+    rows, bps, n_pages = sv.sssd_kv_geometry(a.cfg)
+    keys = uniform_int(92, 1, (n_pages,), 0, 1 << 30).tolist()
+    perm = sorted(range(n_pages), key=lambda i: (keys[i], i))
+    table = torch.tensor(perm[: B * bps], dtype=torch.int32).view(B, bps).to(a.dev)
+    ctxs = [3, 40, 95]
+    for p in (a, b):
+        p.ctx.sssd_kv_set_block_table(table)
+        for i in range(B):
+            p.prefill_random_kv(93, i, ctxs[i])
+    b.ctx.sssd_set_gemm_chain(True)
+    lens = torch.tensor(ctxs, dtype=torch.int32)
+    tokens = uniform_int(94, 1, (B, k + 1), 0, s.vocab - 1)
+    ra, rb = a.step(tokens, lens), b.step(tokens, lens)
+    assert torch.equal(ra["logits"], rb["logits"])
+    for l in range(s.n_layers):
+        for i in range(B):
+            n = ctxs[i] + k + 1
+            Ka = torch.empty(s.n_kv_heads, n, s.head_dim, dtype=torch.bfloat16, device=a.dev)
+            Va, Kb, Vb = torch.empty_like(Ka), torch.empty_like(Ka), torch.empty_like(Ka)
+            a.ctx.sssd_kv_export(l, i, 0, Ka, Va)
+            b.ctx.sssd_kv_export(l, i, 0, Kb, Vb)
+            assert torch.equal(Ka.view(torch.int16), Kb.view(torch.int16)), (l, i)
+            assert torch.equal(Va.view(torch.int16), Vb.view(torch.int16)), (l, i)
+    say("chain + paged cache: logits and appended K/V rows identical to separate launches")
