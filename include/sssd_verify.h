@@ -231,11 +231,11 @@ int sssd_kv_set_block_table(sssd_ctx *ctx, const int32_t *block_table);
 int sssd_set_gemm_chain(sssd_ctx *ctx, int32_t enable);
 
 /* Test aid for the error path above, forced from the host: barrier waits of the chained launches of
- * `ctx` give up after `spin_limit` polls (> 0; default 2^20, about a second), and `epoch_skew` (>= 0)
- * is added to the barrier count the next launches wait for, so that with a skew > 0 no wait can be
- * satisfied and every workgroup leaves through the give-up path: the kernel ends normally, the step's
- * results are void, sssd_verify_sync reports SSSD_EHIP once and restores the default limit. */
-int sssd_debug_chain_wait(sssd_ctx *ctx, int32_t spin_limit, int32_t epoch_skew);
+ * `ctx` give up after `spin_limit` polls (> 0; default 2^20, about a second).  With a limit of 1
+ * only the workgroup that arrives last at a barrier gets through, to give up at the next one: every
+ * workgroup leaves through the give-up path, the kernels end normally, the step's results are void,
+ * and sssd_verify_sync reports SSSD_EHIP once and restores the default limit. */
+int sssd_debug_chain_wait(sssd_ctx *ctx, int32_t spin_limit);
 
 /* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call raised
  * the device flag (and clear it), else SSSD_OK. */

@@ -69,7 +69,7 @@ def lib() -> C.CDLL:
         l.sssd_op_sample.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
         l.sssd_set_gemm_chain.argtypes = [vp, i32]
-        l.sssd_debug_chain_wait.argtypes = [vp, i32, i32]
+        l.sssd_debug_chain_wait.argtypes = [vp, i32]
         l.sssd_kv_geometry.argtypes = [C.POINTER(ModelConfig), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         l.sssd_kv_set_block_table.argtypes = [vp, vp]
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
@@ -217,8 +217,8 @@ class VerifyContext:
     def sssd_set_gemm_chain(self, enable: bool) -> None:
         _check(lib().sssd_set_gemm_chain(self.handle, int(enable)), "sssd_set_gemm_chain")
 
-    def sssd_debug_chain_wait(self, spin_limit: int, epoch_skew: int) -> None:
-        _check(lib().sssd_debug_chain_wait(self.handle, spin_limit, epoch_skew), "sssd_debug_chain_wait")
+    def sssd_debug_chain_wait(self, spin_limit: int) -> None:
+        _check(lib().sssd_debug_chain_wait(self.handle, spin_limit), "sssd_debug_chain_wait")
 
     def sssd_debug_outputs(self, logits: Optional[torch.Tensor], hidden: Optional[torch.Tensor]) -> None:
         _check(lib().sssd_debug_outputs(self.handle, _ptr(logits), _ptr(hidden)), "sssd_debug_outputs")

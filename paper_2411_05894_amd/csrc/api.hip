@@ -65,7 +65,6 @@ struct sssd_ctx {
     int64_t prof_n[SSSD_PROF_CLASSES];
     int device, n_cu;
     int use_chain;                    // O/gate-up/down/next-QKV in one launch when the step allows
-    unsigned long long chain_epoch;   // barriers completed by those launches so far
     int chain_spin_limit;             // polls before a barrier wait of such a launch gives up
 };
 
@@ -374,7 +373,6 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
         INIT_TRY(hipGetDeviceProperties(&prop, c->device));
         c->n_cu = prop.multiProcessorCount;
         c->use_chain = 0;   // measured no faster than the separate launches so far: opt-in (sssd_set_gemm_chain)
-        c->chain_epoch = 0;
         c->chain_spin_limit = 1 << 20;   // on the order of a second
     }
     INIT_TRY(hipStreamSynchronize(s));
@@ -510,7 +508,7 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
         const bool chained = c->use_chain && stream_chain_supported(g, last_epi);
         if (chained) {
             Prof p(c, s, SSSD_PROF_GEMM, true);
-            HIP_TRY(launch_stream_chain(g, last_epi, W.chain_bar, &c->chain_epoch, W.chain_err, c->chain_spin_limit, s, p.start(), p.stop()));
+            HIP_TRY(launch_stream_chain(g, last_epi, W.chain_bar, W.chain_err, c->chain_spin_limit, s, p.start(), p.stop()));
         }
         if (!chained) {
             f = g[0]; HIP_TRY(fgemm(FEPI_RESID));
@@ -614,11 +612,10 @@ int sssd_set_gemm_chain(sssd_ctx *c, int32_t enable)
     return SSSD_OK;
 }
 
-int sssd_debug_chain_wait(sssd_ctx *c, int32_t spin_limit, int32_t epoch_skew)
+int sssd_debug_chain_wait(sssd_ctx *c, int32_t spin_limit)
 {
-    if (!valid(c) || spin_limit <= 0 || epoch_skew < 0) return SSSD_EINVAL;
+    if (!valid(c) || spin_limit <= 0) return SSSD_EINVAL;
     c->chain_spin_limit = spin_limit;
-    c->chain_epoch += (unsigned long long)epoch_skew;
     return SSSD_OK;
 }
 
@@ -632,12 +629,11 @@ int sssd_verify_sync(sssd_ctx *c, void *stream)
     HIP_TRY(hipMemcpyAsync(&chain_flag, c->W.chain_err, 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (chain_flag) {   // a grid barrier of a chained launch gave up: that step's results are void
-        // every launch has ended; the counters no longer match the epoch: start both over, and go
-        // back to separate launches until the caller asks for the chain again
+        // every launch has ended; some workgroups arrived at barriers that others gave up on, so the
+        // counters start over; separate launches until the caller asks for the chain again
         HIP_TRY(hipMemsetAsync(c->W.chain_err, 0, 4, s));
         HIP_TRY(hipMemsetAsync(c->W.chain_bar, 0, 16 * 9 * sizeof(unsigned long long), s));
         HIP_TRY(hipStreamSynchronize(s));
-        c->chain_epoch = 0;
         c->use_chain = 0;
         c->chain_spin_limit = 1 << 20;
         return SSSD_EHIP;

@@ -483,12 +483,11 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 struct ChainArgs {
     FusedGemmArgs g[4];          // O, gate/up, down, then QKV (next layer) or LM
     unsigned long long *bar;     // [0]: groups that arrived; [16*(1+i)]: arrivals of group i (of up to 8), never reset
-    unsigned long long epoch;    // barriers completed by all earlier launches
     int *err;                    // set when a barrier wait gave up
     int spin_limit;              // polls of the top counter before a wait gives up
 };
 
-// Boundary number `index` (0-based) between two GEMMs of this launch: a grid-wide barrier with the
+// Boundary between two GEMMs of a chained launch: a grid-wide barrier with the
 // next GEMM's first weight loads (preload()) issued around it.  Memory operations of a wave retire
 // in order, so anything that waits for a returned value also waits for the weight loads issued
 // before it; hence the order below.  Only the first four waves of a workgroup store results: the
@@ -498,23 +497,28 @@ struct ChainArgs {
 // comes back behind them, the other workgroups have usually arrived.
 // False (for the whole workgroup) when the wait gave up: the caller returns, so the kernel always ends.
 template <typename Preload>
-__device__ __forceinline__ bool chain_boundary(const ChainArgs &c, int index, int *ok_s, int wave, Preload &&preload)
+__device__ __forceinline__ bool chain_boundary(const ChainArgs &c, int *ok_s, unsigned long long *target_s, int wave, Preload &&preload)
 {
     if (wave >= 4) preload();
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's stores have reached memory
     __syncthreads();
-    const unsigned long long t = c.epoch + (unsigned long long)index + 1;
+    // The counters only ever grow.  A workgroup cannot arrive at a barrier before the one in front of
+    // it has completed, so the arrivals a group counter held before this one tell which barrier this
+    // is (of this launch and all earlier ones): no count has to come from the host.
     const unsigned G = gridDim.x < 8 ? gridDim.x : 8;
     if (threadIdx.x == 0) {
         const unsigned g = blockIdx.x % G, members = (gridDim.x - g + G - 1) / G;
         const unsigned long long old =
             __hip_atomic_fetch_add(c.bar + 16 * (1 + g), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long t = old / members + 1;     // barriers completed once this one is
         if (old + 1 == t * members) __hip_atomic_fetch_add(c.bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *target_s = t * G;
     }
     if (wave < 4) preload();
     if (threadIdx.x == 0) {
         int ok = 1, spins = 0;
-        while (__hip_atomic_load(c.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < t * G) {
+        const unsigned long long goal = *target_s;
+        while (__hip_atomic_load(c.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < goal) {
             if (++spins > c.spin_limit) {
                 ok = 0;
                 *c.err = 1;
@@ -625,19 +629,19 @@ __global__ __launch_bounds__(PW * 64) void chain_kernel(ChainArgs c)
     __shared__ float red[2][PW][256];
     __shared__ float rstd_s[16];
     __shared__ int ok_s;
+    __shared__ unsigned long long target_s;   // written and read by thread 0 only
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     u32x4 w[8];
-    int nb = 0;
     chain_preload<FEPI_RESID, 8>(c.g[0], w, wave, lane);
     chain_phase<FEPI_RESID, 8, false, true>(c.g[0], w, red, rstd_s, wave, lane);
-    if (!chain_boundary(c, nb++, &ok_s, wave, [&] { chain_preload<FEPI_SWIGLU, 8>(c.g[1], w, wave, lane); })) return;
+    if (!chain_boundary(c, &ok_s, &target_s, wave, [&] { chain_preload<FEPI_SWIGLU, 8>(c.g[1], w, wave, lane); })) return;
     chain_phase<FEPI_SWIGLU, 8, false, true>(c.g[1], w, red, rstd_s, wave, lane);
-    if (!chain_boundary(c, nb++, &ok_s, wave, [&] { chain_preload<FEPI_RESID, KPW_D>(c.g[2], w, wave, lane); })) return;
+    if (!chain_boundary(c, &ok_s, &target_s, wave, [&] { chain_preload<FEPI_RESID, KPW_D>(c.g[2], w, wave, lane); })) return;
     chain_phase<FEPI_RESID, KPW_D, SPLIT_D, true>(c.g[2], w, red, rstd_s, wave, lane);
-    if (!chain_boundary(c, nb++, &ok_s, wave, [&] { chain_preload<LAST, 8>(c.g[3], w, wave, lane); })) return;
+    if (!chain_boundary(c, &ok_s, &target_s, wave, [&] { chain_preload<LAST, 8>(c.g[3], w, wave, lane); })) return;
     if (SPLIT_D) {
         chain_reduce_resid(c.g[2], wave, lane);
-        if (!chain_boundary(c, nb++, &ok_s, wave, [] {})) return;
+        if (!chain_boundary(c, &ok_s, &target_s, wave, [] {})) return;
     }
     chain_phase<LAST, 8, false, false>(c.g[3], w, red, rstd_s, wave, lane);
 }
@@ -1147,13 +1151,13 @@ bool stream_chain_supported(const FusedGemmArgs (&g)[4], int last_epilogue)
     return true;
 }
 
-hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigned long long *bar, unsigned long long *epoch,
-                               int *err, int spin_limit, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
+hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigned long long *bar, int *err, int spin_limit,
+                               hipStream_t s, hipEvent_t t0, hipEvent_t t1)
 {
     if (!stream_chain_supported(g, last_epilogue)) return hipErrorInvalidValue;
     for (int i = 0; i < 4; ++i)
         if (!g[i].A_hi || !g[i].A_lo || !g[i].W0) return hipErrorInvalidValue;
-    if (!bar || !epoch || !err || !g[0].X || !g[0].out_hi || !g[0].out_lo || !g[0].ssq_out || !g[0].gamma_next || !g[1].W1 ||
+    if (!bar || !err || !g[0].X || !g[0].out_hi || !g[0].out_lo || !g[0].ssq_out || !g[0].gamma_next || !g[1].W1 ||
         !g[1].ssq_in || !g[1].out_hi || !g[1].out_lo || !g[2].X || !g[2].out_hi || !g[2].out_lo || !g[2].ssq_out ||
         !g[2].gamma_next || !g[3].ssq_in)
         return hipErrorInvalidValue;
@@ -1166,7 +1170,7 @@ hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigne
         g[i].J = sp[i].J; g[i].upw = sp[i].upw; g[i].groups = sp[i].groups; g[i].part_rows = 16;
         c.g[i] = g[i];
     }
-    c.bar = bar; c.epoch = *epoch; c.err = err; c.spin_limit = spin_limit > 0 ? spin_limit : 1;
+    c.bar = bar; c.err = err; c.spin_limit = spin_limit > 0 ? spin_limit : 1;
     const bool split = sp[2].J > 1, lm = last_epilogue == FEPI_LM;
     const dim3 grid(n_cu), block(PW * 64);   // one workgroup per compute unit: all resident, as the barriers need
 #define SSSD_CLAUNCH(KPW, SPLIT)                                                                                   \
@@ -1177,9 +1181,7 @@ hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigne
     if (sp[2].kpw == 7) { if (split) SSSD_CLAUNCH(7, true); else SSSD_CLAUNCH(7, false); }
     else { if (split) SSSD_CLAUNCH(8, true); else SSSD_CLAUNCH(8, false); }
 #undef SSSD_CLAUNCH
-    const hipError_t e = hipGetLastError();
-    if (e == hipSuccess) *epoch += 3 + (split ? 1 : 0);   // a launch that did not happen passed no barrier
-    return e;
+    return hipGetLastError();
 }
 
 // Split-K scratch needed for M rows: the largest J * rows * Ntot over the model's GEMMs.
