@@ -262,4 +262,20 @@ def test_cfg5_70b_b16_ctx2048_k8():
     gpu = {"logits": logits.cpu().view(B, k + 1, -1), "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
     err, ex, rows = compare_step(gpu, ref, tokens, seqs=[sample])
     progress(f"cfg5: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+    # k = 0 (16 rows: the small-step kernels, every GEMM with its K split over workgroups and summed by
+    # the last of them to arrive): 30 repetitions must give the same logits bit for bit
+    t1 = tokens[:, :1].contiguous().to(dev)
+    first, bad = None, 0
+    for rep in range(30):
+        ctx_.sssd_verify_step(t1, lens.to(dev), acc, nxt)
+        cur = logits[:B]
+        if first is None:
+            first = cur.clone()
+        else:
+            bad += int(not torch.equal(first, cur))
+    assert ctx_.sssd_verify_sync() == 0
+    assert bad == 0, bad
+    e0 = float((first[sample].cpu() - ref_logits[0, 0]).abs().max())
+    progress(f"cfg5 k=0: 30 steps identical, row 0 of sequence {sample} within {e0:.2e} of the oracle")
+    assert e0 < 2e-2
     ctx_.sssd_verify_destroy()
