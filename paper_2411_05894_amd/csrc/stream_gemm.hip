@@ -87,14 +87,6 @@ template <bool COH, typename T> __device__ __forceinline__ T ld(const T *p)
     return *p;
 }
 
-template <bool COH> __device__ __forceinline__ u32x4 ld_record(const u32x4 *p)
-{
-    if (!COH) return *p;
-    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
-    const unsigned long long x = ld<true>(q), y = ld<true>(q + 1);
-    return u32x4{(uint32_t)x, (uint32_t)(x >> 32), (uint32_t)y, (uint32_t)(y >> 32)};
-}
-
 // One output element pair of a unit: row m, column c of the 16-column tile(s).  v0/v1 are the
 // fp32 results of the unit's first/second tile.  The 16 lanes c = 0..15 of a row are adjacent
 // lanes of one wave (RESID and LM reduce over them).
