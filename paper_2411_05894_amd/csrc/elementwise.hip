@@ -8,19 +8,29 @@
 
 namespace {
 
-// grid = M rows, block = 256.  Row arg-max from the LM head's per-tile partials; the lowest
-// token id wins a tie.
-__global__ __launch_bounds__(256) void row_argmax_kernel(const float *part_val, const int *part_idx, int NT, int32_t *that)
+// grid = M rows, block = 1024.  Row arg-max from the LM head's per-tile partials; the lowest
+// token id wins a tie.  The loads go out eight at a time (the kernel is one memory round trip long
+// per batch, not per element).
+__global__ __launch_bounds__(1024) void row_argmax_kernel(const float *part_val, const int *part_idx, int NT, int32_t *that)
 {
-    __shared__ float sv[4];
-    __shared__ int si[4];
+    __shared__ float sv[16];
+    __shared__ int si[16];
     const size_t row = (size_t)blockIdx.x * NT;
     float bv = -INFINITY;
     int bi = 0x7FFFFFFF;
-    for (int t = threadIdx.x; t < NT; t += blockDim.x) {
-        const float v = part_val[row + t];
-        const int id = part_idx[row + t];
-        if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
+    constexpr int U = 8;
+    for (int t0 = threadIdx.x; t0 < NT; t0 += U * 1024) {
+        float v[U];
+        int id[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * 1024;
+            v[u] = t < NT ? part_val[row + t] : -INFINITY;
+            id[u] = t < NT ? part_idx[row + t] : 0x7FFFFFFF;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (v[u] > bv || (v[u] == bv && id[u] < bi)) { bv = v[u]; bi = id[u]; }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -31,7 +41,7 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(const float *part_val, 
     if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; ++w)
+        for (int w = 1; w < 16; ++w)
             if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
         that[blockIdx.x] = bi;
     }
@@ -291,7 +301,7 @@ hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val,
 {
     (void)D;
     if (part_val) {
-        hipLaunchKernelGGL(row_argmax_kernel, dim3(io.B * (io.k + 1)), dim3(256), 0, s, part_val, part_idx, NT, that);
+        hipLaunchKernelGGL(row_argmax_kernel, dim3(io.B * (io.k + 1)), dim3(1024), 0, s, part_val, part_idx, NT, that);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
