@@ -219,26 +219,9 @@ int sssd_kv_geometry(const sssd_model_config *cfg, int32_t *rows_per_page, int32
                      int32_t *n_pages);
 int sssd_kv_set_block_table(sssd_ctx *ctx, const int32_t *block_table);
 
-/* Optional launch structure for steps of at most 16 rows: a layer's O, gate/up and down projections
- * and the next layer's QKV projection (after the last layer: the LM head) run as ONE launch whose
- * workgroups meet in grid-wide barriers, when only the down projection needs its K split (Sec. 4,
- * App. B: the step is bound by weight IO, and weights, unlike activations, can be requested before
- * a barrier).  Results are bit-identical to the separate launches.  enable != 0 turns it on for
- * `ctx` (default: off; on the measured shapes it is not yet faster).  The launch needs every
- * compute unit of the device free; should a barrier wait ever give up, the kernel still ends, the
- * step's results are void, the next sssd_verify_sync returns SSSD_EHIP and the context goes back to
- * separate launches (the chain can be enabled again afterwards). */
-int sssd_set_gemm_chain(sssd_ctx *ctx, int32_t enable);
-
-/* Test aid for the error path above, forced from the host: barrier waits of the chained launches of
- * `ctx` give up after `spin_limit` polls (> 0; default 2^20, about a second).  With a limit of 1
- * only the workgroup that arrives last at a barrier gets through, to give up at the next one: every
- * workgroup leaves through the give-up path, the kernels end normally, the step's results are void,
- * and sssd_verify_sync reports SSSD_EHIP once and restores the default limit. */
-int sssd_debug_chain_wait(sssd_ctx *ctx, int32_t spin_limit);
-
 /* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call raised
- * the device flag (and clear it), else SSSD_OK. */
+ * the device flag (a sequence that does not fit its cache rows, a token id, parent or page out of
+ * range) and clear it, SSSD_EHIP if the runtime reported an error, else SSSD_OK. */
 int sssd_verify_sync(sssd_ctx *ctx, void *stream);
 
 /* Parity aid.  logits != NULL: every following step also stores its fp32

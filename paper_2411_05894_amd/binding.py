@@ -68,8 +68,6 @@ def lib() -> C.CDLL:
         l.sssd_verify_step_tree_sampled.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(SamplingParams), vp, vp, vp, vp, vp, vp]
         l.sssd_op_sample.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
-        l.sssd_set_gemm_chain.argtypes = [vp, i32]
-        l.sssd_debug_chain_wait.argtypes = [vp, i32]
         l.sssd_kv_geometry.argtypes = [C.POINTER(ModelConfig), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         l.sssd_kv_set_block_table.argtypes = [vp, vp]
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
@@ -213,12 +211,6 @@ class VerifyContext:
 
     def sssd_verify_sync(self) -> int:
         return lib().sssd_verify_sync(self.handle, _stream())
-
-    def sssd_set_gemm_chain(self, enable: bool) -> None:
-        _check(lib().sssd_set_gemm_chain(self.handle, int(enable)), "sssd_set_gemm_chain")
-
-    def sssd_debug_chain_wait(self, spin_limit: int) -> None:
-        _check(lib().sssd_debug_chain_wait(self.handle, spin_limit), "sssd_debug_chain_wait")
 
     def sssd_debug_outputs(self, logits: Optional[torch.Tensor], hidden: Optional[torch.Tensor]) -> None:
         _check(lib().sssd_debug_outputs(self.handle, _ptr(logits), _ptr(hidden)), "sssd_debug_outputs")

@@ -24,8 +24,6 @@ struct Buffers {
     float *part_o, *part_ml, *part_val;
     int *part_idx;
     int32_t *pos_base, *err_flag, *that_dbg, *rope_pos;
-    unsigned long long *chain_bar;   // barrier counters of the chained-GEMM launches (zeroed once, never reset)
-    int32_t *chain_err;
     int *tail_count;   // TAIL_SLOTS split-K arrival counters, zero between launches
     uint32_t *anc;
     float *rope_cs, *ssq1;
@@ -64,8 +62,6 @@ struct sssd_ctx {
     double prof_ms[SSSD_PROF_CLASSES];
     int64_t prof_n[SSSD_PROF_CLASSES];
     int device, n_cu;
-    int use_chain;                    // O/gate-up/down/next-QKV in one launch when the step allows
-    int chain_spin_limit;             // polls before a barrier wait of such a launch gives up
 };
 
 namespace {
@@ -145,8 +141,6 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.rope_pos = (int32_t *)take((size_t)S.m_alloc * 4);
     b.anc = (uint32_t *)take((size_t)S.m_alloc * 4);
     b.err_flag = (int32_t *)take(4);
-    b.chain_bar = (unsigned long long *)take(16 * 9 * sizeof(unsigned long long));
-    b.chain_err = (int32_t *)take(4);
     b.tail_count = (int *)take(TAIL_SLOTS * sizeof(int));
     b.ssq1 = (float *)take((size_t)S.m_alloc * (D.h / 16) * 4);
     b.that_dbg = (int32_t *)take((size_t)S.m_alloc * 4);
@@ -372,8 +366,6 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
         hipDeviceProp_t prop;
         INIT_TRY(hipGetDeviceProperties(&prop, c->device));
         c->n_cu = prop.multiProcessorCount;
-        c->use_chain = 0;   // measured no faster than the separate launches so far: opt-in (sssd_set_gemm_chain)
-        c->chain_spin_limit = 1 << 20;   // on the order of a second
     }
     INIT_TRY(hipStreamSynchronize(s));
     c->magic = MAGIC;
@@ -485,8 +477,7 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
         g.W0 = (const u32x4 *)c->lm_head; g.NT = D.V / 16;
         g.n_units = g.NT; g.Ntot = D.V;
     };
-    // Per layer: QKV, attention, then O, gate/up, down and the NEXT QKV (after the last layer: the LM
-    // head) -- those four in one launch when the step is small enough, else one by one.
+    // Per layer: QKV, attention and its merge, O, gate/up, down; then the LM head.
     set_qkv(f, 0);
     HIP_TRY(fgemm(FEPI_QKV));
     for (int l = 0; l < D.L; ++l) {
@@ -497,31 +488,13 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
             HIP_TRY(launch_attention(D, a, s));
         }
         const bool last = l + 1 == D.L;
-        const int last_epi = last ? FEPI_LM : FEPI_QKV;
-        FusedGemmArgs g[4];
-        g[0] = f; set_o(g[0], l);
-        g[1] = g[0]; set_gate_up(g[1], l);
-        g[2] = g[1]; set_down(g[2], l);
-        g[3] = g[2];
-        if (last) set_lm(g[3]);
-        else set_qkv(g[3], l + 1);
-        const bool chained = c->use_chain && stream_chain_supported(g, last_epi);
-        if (chained) {
-            Prof p(c, s, SSSD_PROF_GEMM, true);
-            HIP_TRY(launch_stream_chain(g, last_epi, W.chain_bar, W.chain_err, c->chain_spin_limit, s, p.start(), p.stop()));
-        }
-        if (!chained) {
-            f = g[0]; HIP_TRY(fgemm(FEPI_RESID));
-            f = g[1]; HIP_TRY(fgemm(FEPI_SWIGLU));
-            f = g[2]; HIP_TRY(fgemm(FEPI_RESID));
-            if (last && c->dbg_hidden)
-                HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
-            f = g[3]; HIP_TRY(fgemm(last_epi));
-        } else {
-            f = g[3];
-            if (last && c->dbg_hidden)   // the LM head leaves the stream as the last down projection wrote it
-                HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
-        }
+        set_o(f, l); HIP_TRY(fgemm(FEPI_RESID));
+        set_gate_up(f, l); HIP_TRY(fgemm(FEPI_SWIGLU));
+        set_down(f, l); HIP_TRY(fgemm(FEPI_RESID));
+        if (last && c->dbg_hidden)
+            HIP_TRY(hipMemcpyAsync(c->dbg_hidden, W.X, (size_t)M * D.h * 4, hipMemcpyDeviceToDevice, s));
+        if (last) { set_lm(f); HIP_TRY(fgemm(FEPI_LM)); }
+        else { set_qkv(f, l + 1); HIP_TRY(fgemm(FEPI_QKV)); }
     }
     if (smp) {
         if (c->dbg_logits)
@@ -605,39 +578,13 @@ int sssd_kv_rollback(sssd_ctx *c, int32_t B, int32_t *lens, const int32_t *accep
     return SSSD_OK;
 }
 
-int sssd_set_gemm_chain(sssd_ctx *c, int32_t enable)
-{
-    if (!valid(c)) return SSSD_EINVAL;
-    c->use_chain = enable != 0;
-    return SSSD_OK;
-}
-
-int sssd_debug_chain_wait(sssd_ctx *c, int32_t spin_limit)
-{
-    if (!valid(c) || spin_limit <= 0) return SSSD_EINVAL;
-    c->chain_spin_limit = spin_limit;
-    return SSSD_OK;
-}
-
 int sssd_verify_sync(sssd_ctx *c, void *stream)
 {
     if (!valid(c)) return SSSD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     int32_t flag = 0;
-    int32_t chain_flag = 0;
     HIP_TRY(hipMemcpyAsync(&flag, c->W.err_flag, 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(&chain_flag, c->W.chain_err, 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    if (chain_flag) {   // a grid barrier of a chained launch gave up: that step's results are void
-        // every launch has ended; some workgroups arrived at barriers that others gave up on, so the
-        // counters start over; separate launches until the caller asks for the chain again
-        HIP_TRY(hipMemsetAsync(c->W.chain_err, 0, 4, s));
-        HIP_TRY(hipMemsetAsync(c->W.chain_bar, 0, 16 * 9 * sizeof(unsigned long long), s));
-        HIP_TRY(hipStreamSynchronize(s));
-        c->use_chain = 0;
-        c->chain_spin_limit = 1 << 20;
-        return SSSD_EHIP;
-    }
     if (flag) {
         HIP_TRY(hipMemsetAsync(c->W.err_flag, 0, 4, s));
         HIP_TRY(hipStreamSynchronize(s));

@@ -71,15 +71,6 @@ size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-lev
 hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,
                               hipEvent_t t1);
 hipError_t launch_stream_epilogue(const FusedGemmArgs &a, int epilogue, hipStream_t s);
-// O, gate/up, down and then `last_epilogue` (FEPI_QKV of the next layer, or FEPI_LM) in one launch:
-// possible when M <= 16 and only the down projection needs a split K (stream_chain_supported).
-// bar: 16 * 9 zero-initialised 64-bit counters that only these launches touch (they only grow, and
-// tell each barrier its own number, so a launch may be replayed); err: set if a barrier wait gave
-// up, which it does after spin_limit polls (about a microsecond each) -- the counters must then be
-// zeroed before the next such launch.
-bool stream_chain_supported(const FusedGemmArgs (&g)[4], int last_epilogue);
-hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigned long long *bar, int *err, int spin_limit,
-                               hipStream_t s, hipEvent_t t0, hipEvent_t t1);
 hipError_t launch_fused_embed(const Dims &D, const StepIO &io, const KvGeom &kv, const uint16_t *embed, const uint16_t *gamma,
                               float *X, uint16_t *A_hi, uint16_t *A_lo, float *ssq, int32_t *pos_base, int32_t *rope_pos,
                               uint32_t *anc, int32_t *err_flag, hipStream_t s);

@@ -34,264 +34,9 @@
 
 #include <hip/hip_ext.h>
 
+#include "gemm_device.h"
+
 namespace {
-
-__device__ __forceinline__ f32x4 mfma(const u32x4 &a, const u32x4 &b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-
-// A "unit" is what one epilogue invocation needs: a rotary tile pair (QKV), a gate tile and its
-// up tile (SWIGLU), or a single tile.
-template <int EPI> struct Unit {
-    static constexpr int TILES = (EPI == FEPI_QKV || EPI == FEPI_SWIGLU) ? 2 : 1;
-};
-
-// Tile index of (unit, part) in the concatenated output [Q | K | V] or [gate | up].
-template <int EPI> __device__ __forceinline__ int unit_tile(const FusedGemmArgs &a, int unit, int part)
-{
-    if (EPI == FEPI_QKV) {
-        const int TH = a.d >> 4, per_head = TH >> 1;
-        return (unit / per_head) * TH + unit % per_head + part * per_head;
-    }
-    if (EPI == FEPI_SWIGLU) return unit + part * a.NT;
-    return unit;
-}
-
-// Packed weights of concatenated tile gt (k-tile 0, lane record 0).
-template <int EPI> __device__ __forceinline__ const u32x4 *tile_weights(const FusedGemmArgs &a, int gt)
-{
-    const size_t stride = (size_t)a.KT * 64;
-    if (EPI == FEPI_QKV) {
-        const int TH = a.d >> 4, nqT = a.nq * TH, nkT = a.nkv * TH;
-        if (gt < nqT) return a.W0 + gt * stride;
-        if (gt < nqT + nkT) return a.W1 + (gt - nqT) * stride;
-        return a.W2 + (gt - nqT - nkT) * stride;
-    }
-    if (EPI == FEPI_SWIGLU) return gt < a.NT ? a.W0 + gt * stride : a.W1 + (gt - a.NT) * stride;
-    return a.W0 + gt * stride;
-}
-
-// Device-scope accesses (COH) for data that a workgroup of the SAME launch on another die wrote or
-// will read: stores go through to memory, loads do not take a line this die cached earlier.  Plain
-// accesses are enough across launches.
-template <bool COH, typename T> __device__ __forceinline__ void st(T *p, T v)
-{
-    if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
-}
-
-template <bool COH, typename T> __device__ __forceinline__ T ld(const T *p)
-{
-    if (COH) return __hip_atomic_load(const_cast<T *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return *p;
-}
-
-// One output element pair of a unit: row m, column c of the 16-column tile(s).  v0/v1 are the
-// fp32 results of the unit's first/second tile.  The 16 lanes c = 0..15 of a row are adjacent
-// lanes of one wave (RESID and LM reduce over them).
-template <int EPI, bool COH = false>
-__device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m, int c, bool valid, float v0, float v1, float rs)
-{
-    if (EPI == FEPI_STORE) {
-        if (valid) a.out[(size_t)m * a.Ntot + unit * 16 + c] = v0;
-    } else if (EPI == FEPI_RESID) {
-        const int n = unit * 16 + c;
-        float xn = 0.f;
-        if (valid) {
-            xn = ld<COH>(a.X + (size_t)m * a.h + n) + v0;
-            st<COH>(a.X + (size_t)m * a.h + n, xn);
-            uint16_t hi, lo;
-            split_bf16(xn * bf16_to_f32(a.gamma_next[n]), hi, lo);
-            const size_t idx = packed_index(m, n, (a.h + 31) >> 5);
-            st<COH>(a.out_hi + idx, hi);
-            st<COH>(a.out_lo + idx, lo);
-        }
-        float ss = xn * xn;
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 16);
-        if (valid && c == 0) st<COH>(a.ssq_out + (size_t)m * (a.h >> 4) + unit, ss);
-    } else if (EPI == FEPI_QKV) {
-        if (!valid) return;
-        const int TH = a.d >> 4, per_head = TH >> 1;
-        int head = unit / per_head;
-        const int pair = unit % per_head;
-        v0 *= rs;
-        v1 *= rs;
-        const int b = m / (a.k + 1), j = m % (a.k + 1);
-        const int pos = a.pos_base[b] + j;              // cache row of node j
-        const int half = a.d >> 1, ch = pair * 16 + c;  // channel of v0; v1 is ch + half
-        if (head < a.nq + a.nkv) {
-            const float2 cs = *reinterpret_cast<const float2 *>(a.rope_cs + ((size_t)a.rope_pos[m] * half + ch) * 2);
-            const float y0 = v0 * cs.x - v1 * cs.y, y1 = v0 * cs.y + v1 * cs.x;
-            if (head < a.nq) {
-                const int g = a.nq / a.nkv, kvh = head / g, hl = head % g, rr = j * g + hl;
-                const size_t qs = ((size_t)b * a.nkv + kvh) * a.q_rows_pad * a.d;
-                uint16_t h0, l0, h1, l1;
-                split_bf16(y0, h0, l0);
-                split_bf16(y1, h1, l1);
-                const size_t i_0 = qs + packed_index(rr, ch, a.d >> 5), i_1 = qs + packed_index(rr, ch + half, a.d >> 5);
-                a.Qp[i_0] = h0; a.Qp_lo[i_0] = l0;
-                a.Qp[i_1] = h1; a.Qp_lo[i_1] = l1;
-            } else {
-                head -= a.nq;
-                uint16_t *kr = a.Kc + kcache_offset(a.kv, b, head, pos, 0);
-                kr[ch] = f32_to_bf16(y0);
-                kr[ch + half] = f32_to_bf16(y1);
-            }
-        } else {
-            head -= a.nq + a.nkv;
-            uint16_t *vv = a.Vc + kv_block_offset(a.kv, kv_page(a.kv, b, pos >> 5), head);
-            vv[vblock_index(pos & 31, ch, a.d)] = f32_to_bf16(v0);
-            vv[vblock_index(pos & 31, ch + half, a.d)] = f32_to_bf16(v1);
-        }
-    } else if (EPI == FEPI_SWIGLU) {
-        if (!valid) return;
-        const float gt = v0 * rs, up = v1 * rs;
-        const float hval = gt / (1.f + __expf(-gt)) * up;
-        uint16_t hi, lo;
-        split_bf16(hval, hi, lo);
-        const size_t idx = packed_index(m, unit * 16 + c, a.KT_out);
-        st<COH>(a.out_hi + idx, hi);
-        st<COH>(a.out_lo + idx, lo);
-    } else {  // FEPI_LM
-        const int n = unit * 16 + c;
-        const float logit = valid ? v0 * rs : -INFINITY;
-        if (valid && a.logits) a.logits[(size_t)m * a.vocab + n] = logit;
-        float bv = logit;
-        int bi = n;
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 16);
-            const int oi = __shfl_xor(bi, off, 16);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        if (valid && c == 0) {
-            a.part_val[(size_t)m * a.NT + unit] = bv;
-            a.part_idx[(size_t)m * a.NT + unit] = bi;
-        }
-    }
-}
-
-// rsqrt(mean(x^2) + eps) of row m from the producer's per-16-column sums of squares; whole wave.
-template <bool COH = false> __device__ __forceinline__ float row_rstd(const FusedGemmArgs &a, int m, int lane)
-{
-    const int NSS = a.h >> 4;
-    float sum = 0.f;
-    if (m < a.M)
-        for (int t = lane; t < NSS; t += 64) sum += ld<COH>(a.ssq_in + (size_t)m * NSS + t);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    return rsqrtf(sum / (float)a.h + a.eps);
-}
-
-// ---- eight columns per thread ----
-struct Vec8 {
-    float v[8];
-};
-
-template <bool COH = false> __device__ __forceinline__ Vec8 load8(const float *p)
-{
-    if (COH) {   // device-scope: four 8-byte loads
-        Vec8 r;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const unsigned long long u = ld<true>(reinterpret_cast<const unsigned long long *>(p) + q);
-            r.v[2 * q] = __uint_as_float((uint32_t)u);
-            r.v[2 * q + 1] = __uint_as_float((uint32_t)(u >> 32));
-        }
-        return r;
-    }
-    const f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
-    return Vec8{{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]}};
-}
-
-template <bool COH = false> __device__ __forceinline__ void store8(float *p, const Vec8 &x)
-{
-    if (COH) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            st<true>(reinterpret_cast<unsigned long long *>(p) + q,
-                     (unsigned long long)__float_as_uint(x.v[2 * q]) | ((unsigned long long)__float_as_uint(x.v[2 * q + 1]) << 32));
-        return;
-    }
-    *reinterpret_cast<f32x4 *>(p) = f32x4{x.v[0], x.v[1], x.v[2], x.v[3]};
-    *reinterpret_cast<f32x4 *>(p + 4) = f32x4{x.v[4], x.v[5], x.v[6], x.v[7]};
-}
-
-template <bool COH = false> __device__ __forceinline__ void st_record(uint16_t *p, const u32x4 &r)
-{
-    if (COH) {
-        st<true>(reinterpret_cast<unsigned long long *>(p), (unsigned long long)r[0] | ((unsigned long long)r[1] << 32));
-        st<true>(reinterpret_cast<unsigned long long *>(p) + 1, (unsigned long long)r[2] | ((unsigned long long)r[3] << 32));
-        return;
-    }
-    *reinterpret_cast<u32x4 *>(p) = r;
-}
-
-// x[0..7] -> one lane record of bf16 hi parts and one of lo parts
-__device__ __forceinline__ void split8(const Vec8 &x, u32x4 &hi, u32x4 &lo)
-{
-    uint32_t h[4], l[4];
-#pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-        uint16_t h0, l0, h1, l1;
-        split_bf16(x.v[e], h0, l0);
-        split_bf16(x.v[e + 1], h1, l1);
-        h[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        l[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-    }
-    hi = u32x4{h[0], h[1], h[2], h[3]};
-    lo = u32x4{l[0], l[1], l[2], l[3]};
-}
-
-__device__ __forceinline__ u32x4 round8(const Vec8 &x)
-{
-    uint32_t h[4];
-#pragma unroll
-    for (int e = 0; e < 8; e += 2) h[e >> 1] = (uint32_t)f32_to_bf16(x.v[e]) | ((uint32_t)f32_to_bf16(x.v[e + 1]) << 16);
-    return u32x4{h[0], h[1], h[2], h[3]};
-}
-
-// Sum of the J slices of 8 columns starting at (row m, column col), slices in order.
-template <bool COH = false> __device__ __forceinline__ Vec8 sum_slices(const FusedGemmArgs &a, int m, int col)
-{
-    const float *p = a.partials + (size_t)m * a.Ntot + col;
-    const size_t jstride = (size_t)a.part_rows * a.Ntot;
-    Vec8 s = load8<COH>(p);
-    for (int j = 1; j < a.J; ++j) {
-        const Vec8 t = load8<COH>(p + j * jstride);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s.v[e] += t.v[e];
-    }
-    return s;
-}
-
-// Residual epilogue on 8 columns (col..col+7 of row m) per thread, v0 = the projection's result there;
-// kg: which 8-column group of its 32-column block the thread holds (lanes kg and kg^1, 16 lanes
-// apart, share a 16-column sum of squares).  Whole waves call this.
-template <bool COH> __device__ __forceinline__ void resid_block(const FusedGemmArgs &a, int m, int col, bool live, int kg, const Vec8 &v0)
-{
-    float ss = 0.f;
-    if (live) {
-        const Vec8 x = load8<COH>(a.X + (size_t)m * a.h + col);
-        Vec8 xn, xg;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            xn.v[e] = x.v[e] + v0.v[e];
-            xg.v[e] = xn.v[e] * bf16_to_f32(a.gamma_next[col + e]);   // caller's array: no alignment assumed
-            ss += xn.v[e] * xn.v[e];
-        }
-        store8<COH>(a.X + (size_t)m * a.h + col, xn);
-        u32x4 hi, lo;
-        split8(xg, hi, lo);
-        const size_t idx = packed_index(m, col, (a.h + 31) >> 5);
-        st_record<COH>(a.out_hi + idx, hi);
-        st_record<COH>(a.out_lo + idx, lo);
-    }
-    ss += __shfl_xor(ss, 16);   // the other 8 columns of the 16-column group
-    if (live && !(kg & 1)) st<COH>(a.ssq_out + (size_t)m * (a.h >> 4) + (col >> 4), ss);
-}
 
 // ------------------------------------------------------------------ M <= 32 ----
 constexpr int PW = 16;  // waves per workgroup
@@ -317,9 +62,10 @@ __device__ __forceinline__ void stream_tile(const u32x4 (&ah)[MT][KPW], const u3
 }
 
 // grid = n_groups * J workgroups of 1024 threads; MT row tiles of 16 (M <= 16*MT).  Workgroup
-// (grp, j) computes units [grp*upw, (grp+1)*upw) over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1
-// (SPLIT) it stores fp32 partial tiles for epi_kernel instead of applying the epilogue, and the
-// unsplit instantiation carries none of that code (the QKV kernel is at the register limit).
+// (grp, j) computes its units over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1 (SPLIT) it stores
+// fp32 partial tiles, and the workgroup of a column group that arrives last sums them and applies the
+// epilogue (epi_kernel does, in a second launch, when the launcher has no arrival counters for it).
+// The unsplit instantiation carries none of that code (the QKV kernel is at the register limit).
 template <int EPI, int KPW, int MT, bool SPLIT>
 __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 {
@@ -454,188 +200,6 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
             }
         }
     }
-}
-
-// ------------------------------------------------- chained GEMMs, M <= 16 ----
-// O -> gate/up -> down -> (QKV of the next layer | LM head) in ONE launch.  Weights do not depend
-// on activations, so each workgroup issues the first weight loads of the next GEMM as soon as its
-// last tile of the current one is in, and only then waits, in a grid-wide barrier, for the
-// activations that GEMM needs: memory keeps streaming through what used to be the tail of one
-// launch, the gap, and the ramp of the next.  Every workgroup of the grid (one per compute unit, all
-// resident) takes part in every barrier; a GEMM uses the first groups*J of them.
-//
-// What one GEMM writes and the next reads crosses dies inside one launch, so those stores are
-// device-scope (st above) and each thread waits for them before it arrives at the barrier.  The
-// residual stream, the sums of squares and the split-K partials are read device-scope as well.  The
-// packed operands, which every workgroup reads in full, go through the caches with plain loads; that
-// is safe because no operand buffer is read twice in one launch (the caller alternates the two
-// hidden-width buffers), so no die can hold an older copy of a line, and each 128-byte line of an
-// operand is written by a single workgroup (a 16-column unit is 512 contiguous bytes of it).
-// The arithmetic, its order, and hence every result are those of the separate launches.
-struct ChainArgs {
-    FusedGemmArgs g[4];          // O, gate/up, down, then QKV (next layer) or LM
-    unsigned long long *bar;     // [0]: groups that arrived; [16*(1+i)]: arrivals of group i (of up to 8), never reset
-    int *err;                    // set when a barrier wait gave up
-    int spin_limit;              // polls of the top counter before a wait gives up
-};
-
-// Boundary between two GEMMs of a chained launch: a grid-wide barrier with the
-// next GEMM's first weight loads (preload()) issued around it.  Memory operations of a wave retire
-// in order, so anything that waits for a returned value also waits for the weight loads issued
-// before it; hence the order below.  Only the first four waves of a workgroup store results: the
-// others request their weights at once.  The first four wait for their stores to reach memory, the
-// workgroup's arrival is counted (the last of each group of workgroups reports to the top counter),
-// and only then do they request their weights too; by the time the polling thread's first read
-// comes back behind them, the other workgroups have usually arrived.
-// False (for the whole workgroup) when the wait gave up: the caller returns, so the kernel always ends.
-template <typename Preload>
-__device__ __forceinline__ bool chain_boundary(const ChainArgs &c, int *ok_s, unsigned long long *target_s, int wave, Preload &&preload)
-{
-    if (wave >= 4) preload();
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's stores have reached memory
-    __syncthreads();
-    // The counters only ever grow.  A workgroup cannot arrive at a barrier before the one in front of
-    // it has completed, so the arrivals a group counter held before this one tell which barrier this
-    // is (of this launch and all earlier ones): no count has to come from the host.
-    const unsigned G = gridDim.x < 8 ? gridDim.x : 8;
-    if (threadIdx.x == 0) {
-        const unsigned g = blockIdx.x % G, members = (gridDim.x - g + G - 1) / G;
-        const unsigned long long old =
-            __hip_atomic_fetch_add(c.bar + 16 * (1 + g), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long t = old / members + 1;     // barriers completed once this one is
-        if (old + 1 == t * members) __hip_atomic_fetch_add(c.bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *target_s = t * G;
-    }
-    if (wave < 4) preload();
-    if (threadIdx.x == 0) {
-        int ok = 1, spins = 0;
-        const unsigned long long goal = *target_s;
-        while (__hip_atomic_load(c.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < goal) {
-            if (++spins > c.spin_limit) {
-                ok = 0;
-                *c.err = 1;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-        }
-        *ok_s = ok;
-    }
-    __syncthreads();
-    return *ok_s != 0;
-}
-
-// First weight tile of this workgroup in GEMM `a` (nothing when it has no part in that GEMM).
-template <int EPI, int KPW> __device__ __forceinline__ void chain_preload(const FusedGemmArgs &a, u32x4 (&w)[8], int wave, int lane)
-{
-    const int J = a.J;
-    if ((int)blockIdx.x >= a.groups * J) return;
-    const int j = blockIdx.x % J, grp = blockIdx.x / J;
-    const int u_begin = EPI == FEPI_LM ? grp * a.upw : grp;
-    const int kt0 = (j * PW + wave) * KPW;
-    const u32x4 *wp = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin, 0)) + lane;
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) w[i] = __builtin_nontemporal_load(wp + (kt0 + i < a.KT ? kt0 + i : a.KT - 1) * 64);
-}
-
-// One GEMM of the chain: pgemm_kernel's walk with the first weight tile already in w and the row
-// scales read device-scope.
-template <int EPI, int KPW, bool SPLIT, bool COH_OUT>
-__device__ __forceinline__ void chain_phase(const FusedGemmArgs &a, u32x4 (&w)[8], float (*red)[PW][256], float *rstd_s, int wave,
-                                             int lane)
-{
-    constexpr int TPU = Unit<EPI>::TILES;
-    constexpr bool RUNS = EPI == FEPI_LM, SCALED = EPI != FEPI_RESID && EPI != FEPI_STORE;
-    const int J = SPLIT ? a.J : 1, groups = a.groups;
-    if ((int)blockIdx.x >= groups * J) return;
-    const int j = SPLIT ? blockIdx.x % J : 0, grp = SPLIT ? blockIdx.x / J : blockIdx.x;
-    const int KT = a.KT, kt0 = (j * PW + wave) * KPW;
-    const int u_begin = RUNS ? grp * a.upw : grp, u_stride = RUNS ? 1 : groups;
-    const int n_mine = RUNS ? (u_begin + a.upw < a.n_units ? a.upw : a.n_units - u_begin) : (a.n_units - grp + groups - 1) / groups;
-    const int n_steps = n_mine * TPU;
-
-    int koff[KPW];
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) koff[i] = (kt0 + i < KT ? kt0 + i : KT - 1) * 64;
-    u32x4 ah[1][KPW], al[1][KPW];
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) {
-        const bool live = kt0 + i < KT;
-        ah[0][i] = live ? a.A_hi[koff[i] + lane] : u32x4{0, 0, 0, 0};
-        al[0][i] = live ? a.A_lo[koff[i] + lane] : u32x4{0, 0, 0, 0};
-    }
-    if (SCALED && !SPLIT) rstd_s[wave] = row_rstd<true>(a, wave, lane);   // published by the first barrier below
-
-    float keep = 0.f;
-    for (int s = 0; s < n_steps; ++s) {
-        const int unit = u_begin + (s / TPU) * u_stride, part = s % TPU;
-        f32x4 acc[1];
-        if (s + 1 < n_steps) {
-            const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + ((s + 1) / TPU) * u_stride, (s + 1) % TPU)) + lane;
-            stream_tile<KPW, 1, true, 8>(ah, al, w, wn, koff, acc);
-        } else {
-            stream_tile<KPW, 1, false, 8>(ah, al, w, nullptr, koff, acc);
-        }
-        float *rb = &red[s & 1][0][0];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) rb[wave * 256 + r * 64 + lane] = acc[0][r];
-        __syncthreads();
-        if (wave < 4) {
-            float v = 0.f;
-#pragma unroll
-            for (int ww = 0; ww < PW; ++ww) v += rb[ww * 256 + wave * 64 + lane];
-            const int m = 4 * (lane >> 4) + (wave & 3), c = lane & 15;
-            if (SPLIT) {
-                st<true>(a.partials + ((size_t)j * a.part_rows + m) * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c, v);
-            } else if (TPU == 2 && part == 0) {
-                keep = v;
-            } else {
-                const float rs = SCALED ? rstd_s[m] : 1.f;
-                if (TPU == 2) epilogue<EPI, COH_OUT>(a, unit, m, c, m < a.M, keep, v, rs);
-                else epilogue<EPI, COH_OUT>(a, unit, m, c, m < a.M, v, 0.f, rs);
-            }
-        }
-    }
-}
-
-// Sum of the K slices of the down projection and its residual epilogue, thread for thread what
-// epi_kernel does (same order of every sum): 32-column block cb by the first wave of workgroup
-// cb % gridDim.
-__device__ __forceinline__ void chain_reduce_resid(const FusedGemmArgs &a, int wave, int lane)
-{
-    if (wave != 0) return;
-    const int m = lane & 15, kg = lane >> 4;
-    for (int cb = blockIdx.x; cb * 32 < a.Ntot; cb += gridDim.x) {
-        const int col = cb * 32 + kg * 8;
-        const bool live = m < a.M && col < a.Ntot;
-        Vec8 v0{};
-        if (live) v0 = sum_slices<true>(a, m, col);
-        resid_block<true>(a, m, col, live, kg, v0);
-    }
-}
-
-// KPW_D/SPLIT_D: the down projection's k-tiles per wave and whether its K is split over workgroups;
-// the other three GEMMs run unsplit with 8 k-tiles per wave.  LAST: FEPI_QKV or FEPI_LM.
-template <int KPW_D, bool SPLIT_D, int LAST>
-__global__ __launch_bounds__(PW * 64) void chain_kernel(ChainArgs c)
-{
-    __shared__ float red[2][PW][256];
-    __shared__ float rstd_s[16];
-    __shared__ int ok_s;
-    __shared__ unsigned long long target_s;   // written and read by thread 0 only
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    u32x4 w[8];
-    chain_preload<FEPI_RESID, 8>(c.g[0], w, wave, lane);
-    chain_phase<FEPI_RESID, 8, false, true>(c.g[0], w, red, rstd_s, wave, lane);
-    if (!chain_boundary(c, &ok_s, &target_s, wave, [&] { chain_preload<FEPI_SWIGLU, 8>(c.g[1], w, wave, lane); })) return;
-    chain_phase<FEPI_SWIGLU, 8, false, true>(c.g[1], w, red, rstd_s, wave, lane);
-    if (!chain_boundary(c, &ok_s, &target_s, wave, [&] { chain_preload<FEPI_RESID, KPW_D>(c.g[2], w, wave, lane); })) return;
-    chain_phase<FEPI_RESID, KPW_D, SPLIT_D, true>(c.g[2], w, red, rstd_s, wave, lane);
-    if (!chain_boundary(c, &ok_s, &target_s, wave, [&] { chain_preload<LAST, 8>(c.g[3], w, wave, lane); })) return;
-    if (SPLIT_D) {
-        chain_reduce_resid(c.g[2], wave, lane);
-        if (!chain_boundary(c, &ok_s, &target_s, wave, [] {})) return;
-    }
-    chain_phase<LAST, 8, false, false>(c.g[3], w, red, rstd_s, wave, lane);
 }
 
 // ---- epilogue from split-K partials ----
@@ -1130,51 +694,6 @@ template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool
 }  // namespace
 
 int stream_gemm_max_rows() { return 32; }
-
-bool stream_chain_supported(const FusedGemmArgs (&g)[4], int last_epilogue)
-{
-    if (g[0].M > 16 || (last_epilogue != FEPI_QKV && last_epilogue != FEPI_LM)) return false;
-    const int n_cu = g[0].n_cu > 0 ? g[0].n_cu : 256;
-    for (int i = 0; i < 4; ++i) {
-        const SmallPlan sp = small_plan(g[i]);
-        if (sp.groups * sp.J > n_cu) return false;
-        if (i != 2 && (sp.J != 1 || sp.kpw != 8)) return false;   // only the down projection may split K or run 7 k-tiles per wave
-    }
-    return true;
-}
-
-hipError_t launch_stream_chain(FusedGemmArgs (&g)[4], int last_epilogue, unsigned long long *bar, int *err, int spin_limit,
-                               hipStream_t s, hipEvent_t t0, hipEvent_t t1)
-{
-    if (!stream_chain_supported(g, last_epilogue)) return hipErrorInvalidValue;
-    for (int i = 0; i < 4; ++i)
-        if (!g[i].A_hi || !g[i].A_lo || !g[i].W0) return hipErrorInvalidValue;
-    if (!bar || !err || !g[0].X || !g[0].out_hi || !g[0].out_lo || !g[0].ssq_out || !g[0].gamma_next || !g[1].W1 ||
-        !g[1].ssq_in || !g[1].out_hi || !g[1].out_lo || !g[2].X || !g[2].out_hi || !g[2].out_lo || !g[2].ssq_out ||
-        !g[2].gamma_next || !g[3].ssq_in)
-        return hipErrorInvalidValue;
-    const int n_cu = g[0].n_cu > 0 ? g[0].n_cu : 256;
-    SmallPlan sp[4];
-    for (int i = 0; i < 4; ++i) sp[i] = small_plan(g[i]);
-    if (sp[2].J > 1 && (size_t)sp[2].J * 16 * g[2].Ntot * sizeof(float) > g[2].partial_bytes) return hipErrorInvalidValue;
-    ChainArgs c{};
-    for (int i = 0; i < 4; ++i) {
-        g[i].J = sp[i].J; g[i].upw = sp[i].upw; g[i].groups = sp[i].groups; g[i].part_rows = 16;
-        c.g[i] = g[i];
-    }
-    c.bar = bar; c.err = err; c.spin_limit = spin_limit > 0 ? spin_limit : 1;
-    const bool split = sp[2].J > 1, lm = last_epilogue == FEPI_LM;
-    const dim3 grid(n_cu), block(PW * 64);   // one workgroup per compute unit: all resident, as the barriers need
-#define SSSD_CLAUNCH(KPW, SPLIT)                                                                                   \
-    do {                                                                                                           \
-        if (lm) hipExtLaunchKernelGGL((chain_kernel<KPW, SPLIT, FEPI_LM>), grid, block, 0, s, t0, t1, 0, c);       \
-        else hipExtLaunchKernelGGL((chain_kernel<KPW, SPLIT, FEPI_QKV>), grid, block, 0, s, t0, t1, 0, c);         \
-    } while (0)
-    if (sp[2].kpw == 7) { if (split) SSSD_CLAUNCH(7, true); else SSSD_CLAUNCH(7, false); }
-    else { if (split) SSSD_CLAUNCH(8, true); else SSSD_CLAUNCH(8, false); }
-#undef SSSD_CLAUNCH
-    return hipGetLastError();
-}
 
 // Split-K scratch needed for M rows: the largest J * rows * Ntot over the model's GEMMs.
 size_t stream_gemm_partial_bytes(const Dims &D, int M)

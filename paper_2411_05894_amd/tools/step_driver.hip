@@ -3,7 +3,7 @@
 // profiler runs that need a plain executable (hardware-counter collection), and it includes
 // a plain copy kernel of known traffic (--copy-gib) to calibrate byte counters against.
 //
-//   step_driver --shape 8b --batch 1 --ctx 2048 --k 8 --steps 5 [--copy-gib 1] [--chain 1]
+//   step_driver --shape 8b --batch 1 --ctx 2048 --k 8 --steps 5 [--copy-gib 1] [--layers n]
 #include "../../include/sssd_verify.h"
 
 #include <hip/hip_runtime.h>
@@ -65,7 +65,7 @@ __global__ void calibration_copy_kernel(const uint4 *src, uint4 *dst, size_t n)
 int main(int argc, char **argv)
 {
     std::string shape = "8b";
-    int B = 1, ctx = 2048, k = 8, steps = 5, warmup = 2, chain = 0;
+    int B = 1, ctx = 2048, k = 8, steps = 5, warmup = 2, layers = 0;
     double copy_gib = 0.0;
     for (int i = 1; i + 1 < argc; i += 2) {
         const std::string f = argv[i];
@@ -77,7 +77,7 @@ int main(int argc, char **argv)
         else if (f == "--steps") steps = std::atoi(v);
         else if (f == "--warmup") warmup = std::atoi(v);
         else if (f == "--copy-gib") copy_gib = std::atof(v);
-        else if (f == "--chain") chain = std::atoi(v);   // 1: the chained launch of the small-step GEMMs
+        else if (f == "--layers") layers = std::atoi(v);   // override the layer count of the shape (shorter runs)
         else { std::fprintf(stderr, "unknown flag %s\n", f.c_str()); return 2; }
     }
     sssd_model_config cfg{};
@@ -85,6 +85,7 @@ int main(int argc, char **argv)
     else if (shape == "70b") { cfg.n_layers = 80; cfg.hidden = 8192; cfg.n_q_heads = 64; cfg.n_kv_heads = 8; cfg.head_dim = 128; cfg.ffn = 28672; cfg.vocab = 128256; cfg.rope_base = 500000.f; }
     else if (shape == "tiny") { cfg.n_layers = 2; cfg.hidden = 256; cfg.n_q_heads = 4; cfg.n_kv_heads = 2; cfg.head_dim = 64; cfg.ffn = 688; cfg.vocab = 1024; cfg.rope_base = 10000.f; }
     else { std::fprintf(stderr, "unknown shape\n"); return 2; }
+    if (layers > 0) cfg.n_layers = layers;
     cfg.rms_eps = 1e-5f; cfg.max_batch = B; cfg.max_k = k; cfg.max_seq = ctx + k + 1;
     const bool in_place = shape == "70b";
 
@@ -128,7 +129,6 @@ int main(int argc, char **argv)
     if (!in_place) CK(hipMalloc(&pk, pk_b));
     sssd_ctx *vc = nullptr;
     SK(sssd_verify_init(&cfg, &w, kv, kv_b, ws, ws_b, pk, in_place ? 0 : pk_b, in_place ? SSSD_PACK_IN_PLACE : 0, &vc));
-    SK(sssd_set_gemm_chain(vc, chain));
     // cache contents: finite pseudo-random rows everywhere (import is not needed for timing)
     hipLaunchKernelGGL(fill_bf16, dim3(4096), dim3(256), 0, 0, (uint16_t *)kv, kv_b / 2, 12345u, 2.4f);
     int32_t *tok, *lens, *acc, *nxt;

@@ -119,28 +119,6 @@ def test_cfg2_shape_paged_cache_is_bit_identical(pair_8b):
 
 
 @pytest.mark.timeout(300)
-def test_8b_shape_chain_is_bit_identical(pair_8b):
-    """The 8B shape (the down projection splits K in four: the chained launch sums the slices
-    itself), B=1, context 2048, k=8 and k=15; then back to separate launches."""
-    p, s = pair_8b, pair_8b.shape
-    p.prefill_random_kv(4, 0, 2048)
-    lens = torch.tensor([2048], dtype=torch.int32)
-    try:
-        for k in (8, 15):
-            tokens = uniform_int(75, 1 + k, (1, k + 1), 0, s.vocab - 1)
-            p.ctx.sssd_set_gemm_chain(False)
-            a = {n: v.clone() for n, v in p.step(tokens, lens).items() if torch.is_tensor(v)}
-            p.ctx.sssd_set_gemm_chain(True)
-            for rep in range(3):
-                b = p.step(tokens, lens)
-                for n in ("logits", "hidden", "accepted_len", "next_token"):
-                    assert torch.equal(a[n], b[n]), (k, rep, n)
-        progress("chain 8b: k=8 and k=15, three chained steps each, bit-identical to separate launches")
-    finally:
-        p.ctx.sssd_set_gemm_chain(False)
-
-
-@pytest.mark.timeout(300)
 def test_8b_shape_split_k_sums_repeat_bit_for_bit(pair_8b):
     """Steps whose GEMMs split K over workgroups (k=8: the down projection; k=16: every GEMM) hand the
     slices from one workgroup to another inside a launch.  200 repetitions of the same step must give
