@@ -73,8 +73,9 @@ int32_t sssd_draft_speculation_length(double peak_flops, double peak_bytes_per_s
 /* ---- introspection for tests (the same numbers the algorithms use) ---- */
 /* Count stored for the n-gram gram[0..n) in the trie of `seq` (0 if absent or n > depth). */
 int64_t sssd_draft_input_count(const sssd_drafter *d, int32_t seq, const int32_t *gram, int32_t n);
-/* Alg. 1: sub-prefixes of the tail that are in the trie; match_len[i] = length of the i-th,
- * longest first; returns how many (<= prefix_len), or a negative code. */
+/* The matches Alg. 1 looks for: suffixes of the sequence (at most prefix_len tokens long) that are
+ * n-grams of its trie, as the library tracks them while appending; match_len[i] = length of the
+ * i-th, longest first; returns how many (<= prefix_len), or a negative code. */
 int32_t sssd_draft_match_input(const sssd_drafter *d, int32_t seq, int32_t *match_len);
 /* Suffix-array range of `prefix` in sub-index `sub` (0 = oldest): positions in the token array
  * of the matching suffixes in suffix-array order, at most max_out of them; *total = their number. */

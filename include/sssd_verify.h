@@ -2,8 +2,8 @@
  * sssd_verify.h -- C ABI of the SSSD verification step on one MI355X (gfx950).
  *
  * The paper (SSSD, arXiv 2411.05894) drafts candidate tokens on the host and
- * has the target model verify "the last generated token and the speculated
- * tokens" in a single forward pass (Sec. 2; Sec. 3.2, first paragraph).  This
+ * has the target model check them in one forward pass over the newest accepted
+ * token followed by the drafts (Sec. 2; Sec. 3.2, first paragraph).  This
  * library is that device-side step for k drafts per sequence, given as a
  * linear chain (sssd_verify_step) or as a draft tree (sssd_verify_step_tree):
  * one pass of a Llama-style decoder over b sequences x s_q = k+1
@@ -34,8 +34,9 @@ extern "C" {
 #define SSSD_OK 0
 #define SSSD_EINVAL (-1)    /* null pointer, bad handle, unsupported shape            */
 #define SSSD_ECAPACITY (-2) /* B > max_batch, k > max_k, buffer too small             */
-#define SSSD_ENOSPACE (-3)  /* some lens[b] + k + 1 > max_seq, or a token id >= vocab
-                               (found on the device, reported by sssd_verify_sync)    */
+#define SSSD_ENOSPACE (-3)  /* some lens[b] + k + 1 > max_seq, or a token id, parent or
+                               page out of range (found on the device, reported by
+                               sssd_verify_sync)                                       */
 #define SSSD_EHIP (-4)      /* a HIP runtime call failed                              */
 
 typedef struct sssd_ctx sssd_ctx; /* opaque, host memory owned by the library */
@@ -107,10 +108,13 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *weights, 
  * rows lens[b] .. lens[b]+k of every layer and does NOT change lens; rows of
  * rejected drafts stay behind as dead data and are overwritten by the next
  * step (sssd_kv_rollback computes the new lens).
- * If some lens[b] + k + 1 > max_seq or a token id is outside [0, vocab), that
- * sequence is processed as if lens = 0 / token = 0 (all accesses stay in
- * bounds), its outputs are meaningless, and a sticky device flag makes the
- * next sssd_verify_sync return SSSD_ENOSPACE.
+ * If some lens[b] is negative or lens[b] + k + 1 > max_seq, that sequence is
+ * rejected: it writes NOTHING to the cache (every live row of every sequence
+ * keeps its bits), it is computed as an empty context so that all accesses
+ * stay in bounds, and its outputs are meaningless.  A token id outside
+ * [0, vocab) is computed as token 0; the rows it writes (lens[b] ..
+ * lens[b]+k) are dead rows in any case.  Either condition sets a sticky
+ * device flag that makes the next sssd_verify_sync return SSSD_ENOSPACE.
  * Steps on the same context must be ordered (same stream, or synchronised).
  */
 int sssd_verify_step(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
@@ -212,7 +216,8 @@ int sssd_kv_commit_tree(sssd_ctx *ctx, int32_t B, int32_t k, int32_t *lens,
  *                It is read on the device when each later call executes (steps, commit,
  *                import/export, sssd_op_attention), so it may be updated in stream order between
  *                calls; entries for blocks a step does not touch are ignored.  An entry outside
- *                [0, n_pages) that a step would use is treated as in range (no fault) and raises the
+ *                [0, n_pages) that a step would use rejects that sequence as a bad lens does (it
+ *                writes nothing to the cache; its reads are forced into the pool) and raises the
  *                sticky flag.  Two sequences of one step must not share a page they write.
  */
 int sssd_kv_geometry(const sssd_model_config *cfg, int32_t *rows_per_page, int32_t *blocks_per_seq,
@@ -229,6 +234,14 @@ int sssd_verify_sync(sssd_ctx *ctx, void *stream);
  * hidden != NULL: and the residual stream after the last layer, device float
  * [B*(k+1)][hidden].  NULL switches a store off again. */
 int sssd_debug_outputs(sssd_ctx *ctx, float *logits, float *hidden);
+/* The logits half of sssd_debug_outputs alone (the hidden-state store keeps its setting). */
+int sssd_debug_logits(sssd_ctx *ctx, float *logits);
+/* that != NULL: every following step also stores the token the step itself chose per row, device
+ * int32 [B*(k+1)] (row b*(k+1)+j): the arg-max the LM-head epilogue and the merge kernel compute
+ * without materialising logits (lowest id among equal logits), or the drawn token in the sampled
+ * step.  This is the vector the acceptance walk consumes, so a test can hold it against an
+ * independent arg-max row by row.  NULL switches the store off. */
+int sssd_debug_argmax(sssd_ctx *ctx, int32_t *that);
 
 /*
  * Copy cache rows in (e.g. a prefilled prompt) or out, enqueued on `stream`.

@@ -16,7 +16,7 @@ taken where it leaves a choice:
     tree has fewer than `max_tree_nodes` nodes (the printed listing re-slices the already shortened
     prefix, which would skip lengths); every sub-index is sampled with step
     max(1, floor(|conts| / (max_samples // sub_indices)));
-  * no draft node lies deeper than branch_len below the root ("max depth of each draft");
+  * no draft node lies deeper than branch_len below the root (branch_len bounds the depth of a draft);
   * dec_len counts the root: it is the speculation length s_q of Sec. 3.2.
 
 Pins (tests/test_oracle_drafter_pins.py): trie counts == brute-force n-gram occurrence counts;

@@ -9,10 +9,10 @@
  * What it computes: one forward pass of a Llama-style decoder over
  * b sequences x s_q = k+1 tokens (the last accepted token followed by k
  * drafts) against a per-sequence KV cache, i.e. the operations listed row by
- * row in the paper's Table 2 (App. B, "Impact of the key variables of the
- * decoding phase") with tensor parallelism p = 1, followed by greedy
- * acceptance (Sec. 2: drafts "are then verified in a single forward pass of
- * the target model ... maintaining the exact output distribution").
+ * row in the paper's Table 2 (App. B, the table of decode-phase operations)
+ * with tensor parallelism p = 1, followed by greedy acceptance (Sec. 2: one
+ * pass of the target model checks all drafts, and what is emitted is exactly
+ * what the target model alone would emit).
  *
  * Arithmetic: values are fp32; every reduction (dot product, sum of squares,
  * softmax denominator) accumulates in fp64 and is rounded to fp32 once.
@@ -341,8 +341,8 @@ void orc_layer_decode_token(const orc_config *c, const orc_layer_weights *w, flo
 /* ------------------------------------------------------------------------
  * Tree verification.  The paper verifies a draft TREE, not a chain (Sec. 3.1:
  * candidates from the input trie and the datastore are merged into a draft
- * tree, from which "the candidate vector for verification and the
- * corresponding attention mask" are built); Table 2's attention row carries
+ * tree, which yields the vector of candidate tokens to verify and the
+ * attention mask that goes with it); Table 2's attention row carries
  * that mask explicitly, M of shape (b, s_q, s_kv + s_q), one byte per element.
  * Node 0 is the root (the last accepted token), parent[i] < i for i = 1..k.
  * A node sees the old cache, its ancestors and itself; its position is

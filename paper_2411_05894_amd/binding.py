@@ -71,6 +71,8 @@ def lib() -> C.CDLL:
         l.sssd_kv_geometry.argtypes = [C.POINTER(ModelConfig), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         l.sssd_kv_set_block_table.argtypes = [vp, vp]
         l.sssd_debug_outputs.argtypes = [vp, vp, vp]
+        l.sssd_debug_logits.argtypes = [vp, vp]
+        l.sssd_debug_argmax.argtypes = [vp, vp]
         l.sssd_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         l.sssd_kv_export.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         l.sssd_profile_enable.argtypes = [vp, i32]
@@ -214,6 +216,12 @@ class VerifyContext:
 
     def sssd_debug_outputs(self, logits: Optional[torch.Tensor], hidden: Optional[torch.Tensor]) -> None:
         _check(lib().sssd_debug_outputs(self.handle, _ptr(logits), _ptr(hidden)), "sssd_debug_outputs")
+
+    def sssd_debug_logits(self, logits: Optional[torch.Tensor]) -> None:
+        _check(lib().sssd_debug_logits(self.handle, _ptr(logits)), "sssd_debug_logits")
+
+    def sssd_debug_argmax(self, that: Optional[torch.Tensor]) -> None:
+        _check(lib().sssd_debug_argmax(self.handle, _ptr(that)), "sssd_debug_argmax")
 
     def sssd_kv_import(self, layer: int, b: int, t0: int, k_src: torch.Tensor, v_src: torch.Tensor) -> None:
         assert k_src.dtype == torch.bfloat16 and k_src.shape == v_src.shape

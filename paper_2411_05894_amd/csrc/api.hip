@@ -56,6 +56,7 @@ struct sssd_ctx {
     uint16_t *Kc, *Vc;
     const int32_t *block_table;   // device [max_batch][blocks_per_seq] or nullptr (contiguous runs of pages)
     float *dbg_logits, *dbg_hidden;
+    int32_t *dbg_that;
     bool prof_on;
     std::vector<ProfEvent> prof_pool;
     size_t prof_used;
@@ -298,6 +299,7 @@ int sssd_verify_init(const sssd_model_config *cfg, const sssd_weights *w, void *
     c->embed = (const uint16_t *)w->embed;
     c->final_norm = (const uint16_t *)w->final_norm;
     c->dbg_logits = c->dbg_hidden = nullptr;
+    c->dbg_that = nullptr;
     c->block_table = nullptr;
     c->prof_on = false;
     c->prof_used = 0;
@@ -390,6 +392,20 @@ int sssd_debug_outputs(sssd_ctx *c, float *logits, float *hidden)
     if (!valid(c)) return SSSD_EINVAL;
     c->dbg_logits = logits;
     c->dbg_hidden = hidden;
+    return SSSD_OK;
+}
+
+int sssd_debug_logits(sssd_ctx *c, float *logits)
+{
+    if (!valid(c)) return SSSD_EINVAL;
+    c->dbg_logits = logits;
+    return SSSD_OK;
+}
+
+int sssd_debug_argmax(sssd_ctx *c, int32_t *that)
+{
+    if (!valid(c)) return SSSD_EINVAL;
+    c->dbg_that = that;
     return SSSD_OK;
 }
 
@@ -506,6 +522,8 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
         Prof p(c, s, SSSD_PROF_ACCEPT);
         HIP_TRY(launch_accept(D, io, W.part_val, W.part_idx, D.V / 16, W.that_dbg, s));
     }
+    if (c->dbg_that)
+        HIP_TRY(hipMemcpyAsync(c->dbg_that, W.that_dbg, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
     return SSSD_OK;
 }
 

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int q = lane >> 4, c = lane & 15;
-    const int len = a.pos_base[b];
+    const int len = max(a.pos_base[b], 0);   // a rejected sequence (< 0) is read as empty
     const int total = len + a.k + 1;
     const int t_begin = split * a.chunk;
     if (t_begin >= total) return;
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(Dims D, AttnArgs a, i
     const int KTq = (D.qd + 31) >> 5;
     const int sg = lane >> 4, cl = lane & 15;
     const int r = task % R, kvh = (task / R) % D.nkv, b = task / (R * D.nkv);
-    const int total = a.pos_base[b] + k + 1;
+    const int total = max(a.pos_base[b], 0) + k + 1;
     const int n_splits = (total + a.chunk - 1) / a.chunk;   // at most 64 (launch_attention)
     const size_t slot0 = ((size_t)b * D.nkv + kvh) * a.n_splits;
 

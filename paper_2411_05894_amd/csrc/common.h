@@ -76,8 +76,9 @@ struct KvGeom {
     const int32_t *table;   // device [max_batch][blocks_per_seq], or nullptr: contiguous runs
     int blocks_per_seq, n_pages, nkv, d;
 };
-// Page of block blk of sequence b, forced into the pool (a bad table entry is reported by the
-// embedding kernel; here it only must not fault).
+// Page of block blk of sequence b, forced into the pool.  The embedding kernel reports a bad table
+// entry and marks its sequence so that no kernel WRITES through it; readers come here and must only
+// not fault.
 __device__ __forceinline__ int kv_page(const KvGeom &g, int b, int blk)
 {
     int page = g.table ? g.table[(size_t)b * g.blocks_per_seq + blk] : b * g.blocks_per_seq + blk;

@@ -3,7 +3,8 @@
 // speculation length (Sec. 3.2).  Plain C++17, no device code: the paper places drafting on the
 // host so that the accelerator only runs the verification pass.
 //
-// Readings where the pseudocode leaves a choice (it is "logically equivalent, not exact"):
+// Readings where the pseudocode leaves a choice (the paper presents it as a logical equivalent of
+// its implementation, not the implementation itself):
 //  * a node's probability is count(node) / count(parent); along a path the factors telescope to
 //    count(v) / count(u), the definition the text gives for a prefix node u and a descendant v;
 //  * children are visited in ascending token id; the queue pops the largest probability, the
@@ -349,21 +350,14 @@ int32_t sssd_draft_match_input(const sssd_drafter *d, int32_t seq, int32_t *matc
 {
     if (!seq_ok(d, seq) || !match_len) return SSSD_EINVAL;
     const Input &in = d->inputs[seq];
-    // Alg. 1 as printed: walk the trie from the root along every sub-prefix of the tail
-    const int len = (int)in.tokens.size(), P = std::min(d->p.prefix_len, len);
+    // Nothing is searched here: appending a token extends the node of every suffix that ended at the
+    // previous token, so tails[m-1] already IS the trie node of the last m tokens (the matches Alg. 1
+    // looks for).  Reported: the suffix lengths sssd_draft_propose seeds its queue from, longest first.
+    const int32_t n_match = std::min<int32_t>((int32_t)in.tails.size(), d->p.prefix_len);
     int32_t found = 0;
-    for (int iter = 0; iter < P; ++iter) {
-        const int n = P - iter;
-        const int32_t *p = in.tokens.data() + (len - n);
-        int32_t node = 0;
-        int i = 0;
-        while (i < n) {
-            const int32_t c = in.trie.child(node, p[i]);
-            if (c < 0) break;
-            node = c;
-            ++i;
-        }
-        if (i == n) match_len[found++] = n;
+    for (int32_t m = n_match; m >= 1; --m) {
+        const TrieNode &nd = in.trie.nodes[in.tails[m - 1]];
+        if (nd.depth == m && nd.count > 0) match_len[found++] = m;
     }
     return found;
 }

@@ -243,20 +243,23 @@ __global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, KvG
     }
     if (threadIdx.x == 0) {
         int len = io.lens[b];
+        bool reject = false;   // the sequence must not write the cache: its rows would land on live data
         if (len < 0 || len + io.k + 1 > D.max_seq) {
-            *err_flag = 1;
+            reject = true;
             len = 0;
         }
         if (j == 0) {
-            pos_base[b] = len;
-            if (kv.table) {   // every page the step reads or writes must lie in the pool
+            if (kv.table && !reject) {   // every page the step reads or writes must lie in the pool
                 const int last_blk = (len + io.k) >> 5;
                 for (int blk = 0; blk <= last_blk; ++blk) {
                     const int page = kv.table[(size_t)b * kv.blocks_per_seq + blk];
-                    if (page < 0 || page >= kv.n_pages) *err_flag = 1;
+                    if (page < 0 || page >= kv.n_pages) reject = true;
                 }
             }
+            // pos_base < 0 marks the rejected sequence for the K/V writers; readers take it as length 0
+            pos_base[b] = reject ? -1 : len;
         }
+        if (reject) *err_flag = 1;
         int depth = j;
         uint32_t vis = 0xFFFFFFFFu >> (31 - j);
         if (io.parents) {

@@ -88,7 +88,8 @@ __device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m
         v0 *= rs;
         v1 *= rs;
         const int b = m / (a.k + 1), j = m % (a.k + 1);
-        const int pos = a.pos_base[b] + j;              // cache row of node j
+        const int base = a.pos_base[b];                 // < 0: a rejected sequence, which must not touch the cache
+        const int pos = base + j;                       // cache row of node j
         const int half = a.d >> 1, ch = pair * 16 + c;  // channel of v0; v1 is ch + half
         if (head < a.nq + a.nkv) {
             const float2 cs = *reinterpret_cast<const float2 *>(a.rope_cs + ((size_t)a.rope_pos[m] * half + ch) * 2);
@@ -102,13 +103,13 @@ __device__ __forceinline__ void epilogue(const FusedGemmArgs &a, int unit, int m
                 const size_t i_0 = qs + packed_index(rr, ch, a.d >> 5), i_1 = qs + packed_index(rr, ch + half, a.d >> 5);
                 st<COH>(a.Qp + i_0, h0); st<COH>(a.Qp_lo + i_0, l0);
                 st<COH>(a.Qp + i_1, h1); st<COH>(a.Qp_lo + i_1, l1);
-            } else {
+            } else if (base >= 0) {
                 head -= a.nq;
                 uint16_t *kr = a.Kc + kcache_offset(a.kv, b, head, pos, 0);
                 st<COH>(kr + ch, f32_to_bf16(y0));
                 st<COH>(kr + ch + half, f32_to_bf16(y1));
             }
-        } else {
+        } else if (base >= 0) {
             head -= a.nq + a.nkv;
             uint16_t *vv = a.Vc + kv_block_offset(a.kv, kv_page(a.kv, b, pos >> 5), head);
             st<COH>(vv + vblock_index(pos & 31, ch, a.d), f32_to_bf16(v0));

@@ -1,9 +1,9 @@
 // Target-only speculative sampling: one token per tree node drawn from the target model's own
 // distribution (temperature, top-k, top-p), so that acceptance needs no draft probabilities.
 //
-// The paper evaluates SSSD beyond greedy decoding with "a simplified speculative sampling procedure
-// ... which preserves the target distribution without requiring draft probability estimates"
-// (Sec. 4.4, with temperature 0.6 / top-p 0.95; Fig. 5 uses temperature 0.7, top-p 0.8, top-k 20).
+// Beyond greedy decoding the paper runs SSSD with a reduced form of speculative sampling that keeps
+// the target distribution exact and needs no probabilities from the draft side (Sec. 4.4, at
+// temperature 0.6 / top-p 0.95; Fig. 5 uses temperature 0.7, top-p 0.8, top-k 20).
 // n-gram drafts carry no probabilities: the draft distribution of a proposed token is a point mass,
 // for which the acceptance test of speculative sampling (accept with probability min(1, p/q), else
 // resample from the normalised residual) is the same as drawing ONE token t from the target

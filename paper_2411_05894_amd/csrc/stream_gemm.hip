@@ -301,7 +301,8 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int blocks_pe
                 int head = cb / bph;
                 const int ch = col - head * a.d;              // first-half channel of v0[0]
                 const int b = m / (a.k + 1), j = m % (a.k + 1);
-                const int pos = a.pos_base[b] + j;            // cache row of node j
+                const int base = a.pos_base[b];               // < 0: a rejected sequence, which must not touch the cache
+                const int pos = base + j;                     // cache row of node j
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { v0.v[e] *= rs; v1.v[e] *= rs; }
                 if (head < a.nq + a.nkv) {
@@ -323,13 +324,13 @@ __global__ __launch_bounds__(256) void epi_kernel(FusedGemmArgs a, int blocks_pe
                         const size_t i_0 = qs + packed_index(rr, ch, a.d >> 5), i_1 = qs + packed_index(rr, ch + half, a.d >> 5);
                         *reinterpret_cast<u32x4 *>(a.Qp + i_0) = h0; *reinterpret_cast<u32x4 *>(a.Qp_lo + i_0) = l0;
                         *reinterpret_cast<u32x4 *>(a.Qp + i_1) = h1; *reinterpret_cast<u32x4 *>(a.Qp_lo + i_1) = l1;
-                    } else {
+                    } else if (base >= 0) {
                         head -= a.nq;
                         uint16_t *kr = a.Kc + kcache_offset(a.kv, b, head, pos, 0);
                         *reinterpret_cast<u32x4 *>(kr + ch) = round8(y0);
                         *reinterpret_cast<u32x4 *>(kr + ch + half) = round8(y1);
                     }
-                } else {
+                } else if (base >= 0) {
                     head -= a.nq + a.nkv;
                     uint16_t *vv = a.Vc + kv_block_offset(a.kv, kv_page(a.kv, b, pos >> 5), head);
 #pragma unroll

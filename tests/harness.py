@@ -13,6 +13,27 @@ from sssd_synth import (MODEL_SHAPES, TensorId, global_weight_specs, layer_weigh
 
 LOGIT_TOL = 2e-2      # max abs logit error allowed (bf16 kernels vs fp32 oracle)
 MARGIN = 1e-2         # token ids must agree wherever the oracle's top-2 margin exceeds this
+MAX_EXEMPT_FRAC = 0.25  # at most this share of the compared rows (and never all of them) may be undecided
+
+
+def check_exempt(exempt: int, rows: int):
+    """The id rule only binds rows the oracle decides by more than MARGIN.  Which rows those are depends
+    on the oracle alone, so a kernel fault cannot enlarge the set; the bound keeps a test from passing on
+    too few decided rows (seeded inputs at vocab 128256 leave about 4 % of rows undecided)."""
+    limit = max(1, int(MAX_EXEMPT_FRAC * rows))
+    assert exempt <= limit and (rows == 1 or exempt < rows), f"{exempt} of {rows} rows undecided (limit {limit})"
+
+
+def check_fused_argmax(that, gl, ref_that, decided, where):
+    """`that` is the vector the step's own arg-max kernels produced (never read back from stored logits).
+    Every row must pick a maximum of the step's own logits; decided rows must pick the oracle's token."""
+    for j, t in enumerate(that):
+        assert 0 <= t < gl.shape[-1], f"fused arg-max out of range at {where},{j}"
+        assert float(gl[j, t]) == float(gl[j].max()), f"fused arg-max is not a maximum of the logits at ({where},{j})"
+        first = int((gl[j] == gl[j].max()).nonzero()[0])
+        assert t == first, f"fused arg-max does not take the lowest id among equal logits at ({where},{j})"
+        if j < len(decided) and decided[j]:
+            assert t == int(ref_that[j]), f"fused arg-max differs from the oracle at ({where},{j})"
 
 
 def gen_weights(shape, seed: int, device, unit_gains: bool = True):
@@ -45,7 +66,9 @@ class Pair:
         M = max_batch * (max_k + 1)
         self.logits = torch.zeros(M, shape.vocab, dtype=torch.float32, device=dev)
         self.hidden = torch.zeros(M, shape.hidden, dtype=torch.float32, device=dev)
+        self.that = torch.full((M,), -1, dtype=torch.int32, device=dev)
         self.ctx.sssd_debug_outputs(self.logits, self.hidden)
+        self.ctx.sssd_debug_argmax(self.that)
 
     def prefill_random_kv(self, seed: int, b: int, n_rows: int, oracle_slot: Optional[int] = None):
         """Cache rows 0..n_rows-1 of sequence b <- N(0,1) bf16, in both caches."""
@@ -71,7 +94,7 @@ class Pair:
         assert rc == 0, sv.strerror(rc)
         M = B * sq
         return {"logits": self.logits[:M].cpu().view(B, sq, -1), "hidden": self.hidden[:M].cpu().view(B, sq, -1),
-                "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
+                "that": self.that[:M].cpu().view(B, sq), "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
 
 
 def step_tree(pair: "Pair", tokens: torch.Tensor, parents: torch.Tensor, lens: torch.Tensor):
@@ -89,7 +112,7 @@ def step_tree(pair: "Pair", tokens: torch.Tensor, parents: torch.Tensor, lens: t
     assert rc == 0, sv.strerror(rc)
     M = B * sq
     return {"logits": pair.logits[:M].cpu().view(B, sq, -1), "hidden": pair.hidden[:M].cpu().view(B, sq, -1),
-            "accepted_len": acc.cpu(), "next_token": nxt.cpu(), "path": path.cpu(),
+            "that": pair.that[:M].cpu().view(B, sq), "accepted_len": acc.cpu(), "next_token": nxt.cpu(), "path": path.cpu(),
             "dev": {"accepted_len": acc, "path": path}}
 
 
@@ -124,6 +147,8 @@ def compare_tree_step(gpu: Dict[str, torch.Tensor], ref: Dict[str, torch.Tensor]
                 assert int(gl[j].argmax()) == int(ref["that"][b, j]), f"argmax differs at ({b},{j})"
             else:
                 exempt += 1
+        if "that" in gpu:
+            check_fused_argmax(gpu["that"][b].tolist(), gl, ref["that"][b], decided, b)
         ref_path = ref["path"][b]
         n = int(gpu["accepted_len"][b])
         g_path = gpu["path"][b].tolist()
@@ -161,6 +186,8 @@ def compare_step(gpu: Dict[str, torch.Tensor], ref: Dict[str, torch.Tensor], tok
                 assert int(gl[j].argmax()) == int(ref["that"][i, j]), f"argmax differs at ({b},{j})"
             else:
                 exempt += 1
+        if "that" in gpu:
+            check_fused_argmax(gpu["that"][b].tolist(), gl, ref["that"][i], row_ok, b)
         # acceptance walks rows 0..acc; it is pinned when the oracle covers those rows and all are decided
         acc_ref = int(ref["accepted_len"][i])
         if (sq_ref == sq or acc_ref < sq_ref - 1) and all(row_ok[: acc_ref + 1]):

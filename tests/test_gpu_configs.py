@@ -18,7 +18,7 @@ from sssd_synth import (MODEL_SHAPES, TensorId, global_weight_specs, layer_weigh
                         make_weight, uniform_int)
 
 sys.path.insert(0, os.path.dirname(__file__))
-from harness import LOGIT_TOL, Pair, compare_step, compare_tree_step, step_tree  # noqa: E402
+from harness import LOGIT_TOL, Pair, check_exempt, compare_step, compare_tree_step, step_tree  # noqa: E402
 
 DEV = "cuda:0"
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -57,6 +57,7 @@ def test_cfg2_8b_b1_ctx2048_k_sweep(pair_8b):
     t = time.time()
     ref = p.oracle.verify_step(tokens, lens)
     progress(f"cfg2: oracle k=16 took {time.time() - t:.1f}s")
+    ex_all, rows_all = 0, 0
     for k in (16, 8, 3, 0):
         tk = tokens[:, : k + 1].contiguous()
         sub = {"logits": ref["logits"][:, : k + 1], "that": ref["that"][:, : k + 1]}
@@ -65,6 +66,8 @@ def test_cfg2_8b_b1_ctx2048_k_sweep(pair_8b):
         gpu = p.step(tk, lens)
         err, ex, rows = compare_step(gpu, sub, tk)
         progress(f"cfg2 k={k}: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+        ex_all, rows_all = ex_all + ex, rows_all + rows
+    check_exempt(ex_all, rows_all)
 
 
 @pytest.mark.timeout(300)
@@ -89,6 +92,7 @@ def test_cfg2_shape_draft_tree_k16(pair_8b):
     gpu = step_tree(p, tokens, parents, lens)
     err, ex, rows = compare_tree_step(gpu, ref, tokens, parents)
     progress(f"cfg2-tree k={k}: max logit err {err:.2e}, exempt rows {ex}/{rows}, accepted {int(ref['accepted_len'][0])}")
+    check_exempt(ex, rows)
     assert int(ref["accepted_len"][0]) >= 1
 
 
@@ -163,6 +167,7 @@ def test_cfg3_8b_b32_ragged_k4(pair_8b):
     progress(f"cfg3: oracle on 2 sequences took {time.time() - t:.1f}s")
     err, ex, rows = compare_step(gpu, ref, tokens, seqs=sample)
     progress(f"cfg3: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+    check_exempt(ex, rows)
 
 
 @pytest.mark.timeout(300)
@@ -183,6 +188,7 @@ def test_cfg4_8b_b4_ctx32768_k8():
     progress(f"cfg4: oracle on 1 sequence took {time.time() - t:.1f}s")
     err, ex, rows = compare_step(gpu, ref, tokens, seqs=[2])
     progress(f"cfg4: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+    check_exempt(ex, rows)
     p.ctx.sssd_verify_destroy()
 
 
@@ -232,14 +238,28 @@ def test_cfg5_70b_b16_ctx2048_k8():
         torch.cuda.synchronize()
     progress("cfg5: prefilled")
     logits = torch.zeros(B * (k + 1), s.vocab, dtype=torch.float32, device=dev)
-    ctx_.sssd_debug_outputs(logits, None)
+    fused = torch.full((B * (k + 1),), -1, dtype=torch.int32, device=dev)
+    ctx_.sssd_debug_logits(logits)
+    ctx_.sssd_debug_argmax(fused)
     acc = torch.empty(B, dtype=torch.int32, device=dev)
     nxt = torch.empty(B, dtype=torch.int32, device=dev)
-    ctx_.sssd_verify_step(tokens.to(dev), lens.to(dev), acc, nxt)
-    assert ctx_.sssd_verify_sync() == 0
-    gpu = {"logits": logits.cpu().view(B, k + 1, -1), "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
-    err, ex, rows = compare_step(gpu, ref, tokens, seqs=[sample])
-    progress(f"cfg5: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+    # every k the benchmark sweeps at this configuration beyond 0 (k = 0 follows): M = 144, 80 and 48 rows
+    for kk in (8, 4, 2):
+        tk = tokens[:, : kk + 1].contiguous()
+        n_ref = min(kk, k_ref) + 1
+        sub = {"logits": ref_logits[:, :n_ref], "that": that[:, :n_ref]}
+        a, n = oracle.accept(tk[sample, :n_ref].tolist(), that[0, :n_ref].tolist())
+        sub["accepted_len"], sub["next_token"] = torch.tensor([a]), torch.tensor([n])
+        ctx_.sssd_verify_step(tk.to(dev), lens.to(dev), acc, nxt)
+        assert ctx_.sssd_verify_sync() == 0
+        M = B * (kk + 1)
+        gpu = {"logits": logits[:M].cpu().view(B, kk + 1, -1), "that": fused[:M].cpu().view(B, kk + 1),
+               "accepted_len": acc.cpu(), "next_token": nxt.cpu()}
+        err, ex, rows = compare_step(gpu, sub, tk, seqs=[sample])
+        progress(f"cfg5 k={kk}: max logit err {err:.2e}, exempt rows {ex}/{rows}")
+        check_exempt(ex, rows)
+        # every sequence, not only the sampled one: the fused arg-max must be the arg-max of the step's logits
+        assert torch.equal(gpu["that"], gpu["logits"].argmax(-1).to(torch.int32))
     # k = 0 (16 rows: the small-step kernels, every GEMM with its K split over workgroups and summed by
     # the last of them to arrive): 30 repetitions must give the same logits bit for bit
     t1 = tokens[:, :1].contiguous().to(dev)

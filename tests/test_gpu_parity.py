@@ -45,7 +45,7 @@ def test_gemm_vs_oracle(N, K):
     w = normal_bf16(21, N * 3 + K, (N, K), 0.02, device=DEV)
     wp = sv.sssd_op_pack_weight(w)
     wc = w.cpu()
-    for M in (1, 5, 17, 36, 100, 160, 163):
+    for M in (1, 5, 17, 32, 33, 36, 48, 80, 96, 100, 128, 160, 163):
         say(f"gemm N={N} K={K} M={M}")
         x = normal_bf16(22, M * 7 + K, (M, K), 1.0, device=DEV).float() * 1.25
         x += 2.0 ** -10 * normal_bf16(23, M + K, (M, K), 1.0, device=DEV).float()     # not bf16-representable
@@ -175,6 +175,29 @@ def test_tiny_batched_ragged_and_rollback():
     compare_step(gpu2, ref2, tok2)
 
 
+@pytest.mark.parametrize("B,k", [(6, 7), (5, 15), (8, 12), (7, 15), (4, 31)])
+def test_tiny_steps_across_the_row_tilings(B, k):
+    """Whole steps with M = B*(k+1) = 48, 80, 104, 112, 128 rows: past the small-step GEMM kernel
+    (M <= 32), through every row-tile count of the large-M kernel up to the largest step a tiny
+    context of max_k = 31 allows, ragged contexts included."""
+    s = MODEL_SHAPES["tiny"]
+    p = Pair(s, seed=5, max_batch=B, max_k=k, max_seq=260, unit_gains=False)
+    ctxs = [int(c) for c in uniform_int(14, B * 100 + k, (B,), 0, 200)]
+    ctxs[0] = 0
+    for b in range(B):
+        p.prefill_random_kv(15, b, ctxs[b], oracle_slot=b)
+    lens = torch.tensor(ctxs, dtype=torch.int32)
+    tokens = uniform_int(16, B * 100 + k, (B, k + 1), 0, s.vocab - 1)
+    ref = p.oracle.verify_step(tokens, lens, return_hidden=True)
+    gpu = p.step(tokens, lens)
+    e, ex, r = compare_step(gpu, ref, tokens)
+    herr = (gpu["hidden"] - ref["hidden"]).abs().max().item() / ref["hidden"].abs().max().item()
+    say(f"tiny M={B * (k + 1)} (B={B}, k={k}): worst logit err {e:.2e}, hidden rel err {herr:.2e}, exempt {ex}/{r}")
+    assert herr < 5e-3
+    assert ex < r // 2
+    p.ctx.sssd_verify_destroy()
+
+
 def test_error_reporting():
     s = MODEL_SHAPES["tiny"]
     p = Pair(s, seed=1, max_batch=2, max_k=4, max_seq=64)
@@ -193,6 +216,57 @@ def test_error_reporting():
     with pytest.raises(sv.SssdError) as ei:
         p.ctx.sssd_verify_step(torch.zeros(2, 6, dtype=torch.int32, device=DEV), lens, out, out)
     assert ei.value.code == sv.SSSD_ECAPACITY
+
+
+def _export_all(p, b, n_rows):
+    s = p.shape
+    out = []
+    for l in range(s.n_layers):
+        K = torch.empty(s.n_kv_heads, n_rows, s.head_dim, dtype=torch.bfloat16, device=DEV)
+        V = torch.empty_like(K)
+        p.ctx.sssd_kv_export(l, b, 0, K, V)
+        out += [K.cpu().view(torch.int16), V.cpu().view(torch.int16)]
+    return out
+
+
+def test_rejected_sequence_leaves_the_cache_untouched():
+    """A sequence whose lens does not fit (or whose block table names a page outside the pool) must not
+    write a single cache row, of its own or of a neighbour: after the flagged step every row of the
+    rejected sequence and every LIVE row of the accepted one hold the bits they held before, and the
+    accepted sequence still gets the oracle's logits."""
+    s = MODEL_SHAPES["tiny"]
+    k, max_seq = 4, 64
+    p = Pair(s, seed=1, max_batch=2, max_k=k, max_seq=max_seq)
+    p.prefill_random_kv(17, 0, 40, oracle_slot=0)
+    p.prefill_random_kv(17, 1, max_seq)
+    tokens = uniform_int(18, 1, (2, k + 1), 0, s.vocab - 1)
+    ref = p.oracle.verify_step(tokens[:1].contiguous(), torch.tensor([40]))
+    rows, bps, n_pages = sv.sssd_kv_geometry(p.cfg)
+    bad_table = torch.arange(2 * bps, dtype=torch.int32).view(2, bps)
+    bad_table[1, 1] = n_pages + 5                                       # block 1 of sequence 1: outside the pool
+    cases = [("lens too large", torch.tensor([40, 61], dtype=torch.int32), None),
+             ("negative lens", torch.tensor([40, -3], dtype=torch.int32), None),
+             ("page outside the pool", torch.tensor([40, 30], dtype=torch.int32), bad_table)]
+    for name, lens, table in cases:
+        before0, before1 = _export_all(p, 0, 40), _export_all(p, 1, 32 if table is not None else max_seq)
+        if table is not None:
+            p.ctx.sssd_kv_set_block_table(table.to(DEV))
+        t = tokens.to(DEV)
+        acc = torch.empty(2, dtype=torch.int32, device=DEV)
+        nxt = torch.empty(2, dtype=torch.int32, device=DEV)
+        p.ctx.sssd_verify_step(t, lens.to(DEV), acc, nxt)
+        assert p.ctx.sssd_verify_sync() == sv.SSSD_ENOSPACE, name
+        # block 0 of sequence 1 is a good page in every case; with the bad table only it can be exported
+        after0, after1 = _export_all(p, 0, 40), _export_all(p, 1, 32 if table is not None else max_seq)
+        p.ctx.sssd_kv_set_block_table(None)
+        assert all(torch.equal(a, b) for a, b in zip(before0, after0)), name
+        assert all(torch.equal(a, b) for a, b in zip(before1, after1)), name
+        if table is not None:   # the rest of sequence 1, through the plain layout the table mirrored
+            assert all(torch.equal(a, b) for a, b in zip(full1, _export_all(p, 1, max_seq))), name
+        full1 = _export_all(p, 1, max_seq)
+        err = (p.logits[: k + 1].cpu() - ref["logits"][0]).abs().max().item()
+        assert err <= LOGIT_TOL, (name, err)
+        say(f"rejected sequence ({name}): cache bits unchanged, neighbour's logits within {err:.2e}")
 
 
 def test_step_is_deterministic():

@@ -127,6 +127,10 @@ def test_sampled_tree_step_vs_oracle():
         # the library's own walk is consistent with its own samples
         mine = [oracle.sample_row(logits[b, j], T, top_k, top_p, float(u[b, j]), w_noise=MARGIN_SAME_LOGITS)
                 for j in range(k + 1)]
+        drawn = p.that[b * (k + 1): (b + 1) * (k + 1)].cpu().tolist()      # the step's own per-row draws
+        for j in range(k + 1):
+            if mine[j][1] > MARGIN_SAME_LOGITS:
+                assert drawn[j] == mine[j][0], f"row ({b},{j}): step drew {drawn[j]}, oracle on the same logits {mine[j][0]}"
         robust = [oracle.sample_row(ref["logits"][b, i], T, top_k, top_p, float(u[b, i]), w_noise=noise, logit_noise=2 * err)[1]
                   for i in ref["path"][b]]
         decided = all(m > noise for m in robust)
