@@ -20,10 +20,6 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each
-# calibrated against a 1 GiB copy kernel); source: profiles/verify_step_8b_b1_ctx2048_k8_hbm_traffic.md.
-# Only the workload those runs covered has a figure.
-MEASURED_TRAFFIC_PER_LAUNCH = {("cfg2", 8, "pgemm_kernel"): 120.50e6}
 
 WORKLOADS = {
     # name: (shape, B, ctx spec, k, k sweep)
@@ -47,6 +43,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (known traffic) to calibrate rocprofv3 byte counters")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel measured by rocprofv3 --pmc runs of THIS command "
+                         "(FETCH_SIZE + WRITE_SIZE, calibrated); reported as roofline.traffic, which is null without it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -124,6 +123,46 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / n_steps
 
+    def quantiles(xs):
+        xs = sorted(xs)
+        pick = lambda q: xs[min(len(xs) - 1, int(round(q * (len(xs) - 1))))]
+        return {"median": round(pick(0.5), 4), "p10": round(pick(0.1), 4), "p90": round(pick(0.9), 4), "n": len(xs)}
+
+    def step_quantiles(kk: int, n_steps: int):
+        """One HIP event pair per step, on the stream the step is launched on (torch's current stream)."""
+        tok = tokens_for(kk)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+        for a, b in ev:
+            a.record()
+            ctx.sssd_verify_step(tok, lens, acc, nxt)
+            b.record()
+        torch.cuda.synchronize()
+        return quantiles([a.elapsed_time(b) for a, b in ev])
+
+    def stream_figures():
+        """What plain kernels reach on this device in this run: a read-only pass (the library's own
+        yardstick kernel) and a device-to-device copy, over 2 GiB each, median of 10."""
+        n = 1 << 31
+        src = torch.zeros(n, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        rd, cp = [], []
+        for i in range(13):
+            a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            a.record()
+            sv.sssd_op_stream_read(src, sink)
+            b.record()
+            dst.copy_(src)
+            c.record()
+            torch.cuda.synchronize()
+            if i >= 3:
+                rd.append(a.elapsed_time(b))
+                cp.append(b.elapsed_time(c))
+        rd.sort(), cp.sort()
+        del src, dst
+        torch.cuda.empty_cache()
+        return n / (rd[len(rd) // 2] * 1e-3) / 1e9, 2 * n / (cp[len(cp) // 2] * 1e-3) / 1e9
+
     if args.pmc_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
@@ -144,6 +183,8 @@ def main() -> int:
     # ---- the timed region ----
     ms = time_steps(k, args.warmup, args.steps)
     assert ctx.sssd_verify_sync() == 0
+    step_q = step_quantiles(k, args.steps)
+    read_gbps, copy_gbps = stream_figures()
     M = B * (k + 1)
     value = M / (ms * 1e-3)
     bytes_alg = cm.algorithmic_bytes(dims, lens_cpu.tolist(), k)
@@ -157,13 +198,16 @@ def main() -> int:
     prof = ctx.sssd_profile_read()
     ctx.sssd_profile_enable(False)
     # dominant kernel: the weight streamer (one launch per GEMM; every weight byte is read once)
-    kname, launches = ("pgemm_kernel" if M <= 16 else "qgemm_kernel"), prof["gemm"]["launches"] / prof_steps
+    small = M <= sv.sssd_op_gemm_small_step_rows()
+    kname, launches = ("pgemm_kernel" if small else "qgemm_kernel"), prof["gemm"]["launches"] / prof_steps
     ms_per_launch = prof["gemm"]["ms"] / prof["gemm"]["launches"]
     bytes_per_launch = bytes_alg["weights"] / launches
     achieved = bytes_per_launch / (ms_per_launch * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                 "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((args.workload, k, kname)),
+                "traffic": args.traffic_bytes,
+                "stream_read_gbps": round(read_gbps, 1), "stream_copy_gbps": round(copy_gbps, 1),
+                "frac_of_achievable": round(achieved / read_gbps, 4),
                 "bytes_per_launch": round(bytes_per_launch), "launches_per_step": launches,
                 "avg_launch_us": round(ms_per_launch * 1e3, 2)}
     classes_ms = {n: round(v["ms"] / prof_steps, 4) for n, v in prof.items()}
@@ -195,9 +239,10 @@ def main() -> int:
     draft_us = (time.perf_counter() - t) * 1e6 / n_prop
 
     # ---- latency curve over k ----
-    curve = {}
+    curve, curve_q = {}, {}
     for kk in sweep:
         curve[kk] = ms if kk == k else time_steps(kk, 3, args.sweep_steps)
+        curve_q[str(kk)] = step_q if kk == k else step_quantiles(kk, args.sweep_steps)
     ratio = {str(kk): round(v / curve[0], 4) for kk, v in curve.items()} if 0 in curve else None
 
     # ---- the oracle, timed on this machine's host cores on a bounded sample ----
@@ -227,7 +272,7 @@ def main() -> int:
     out = {
         "metric": "verified tokens/s of the verify step (B*(k+1) positions per step)",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms, 4), "step_ms_events": step_q, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {wl['shape']}-shaped decoder, B={B}, KV context {wl['ctx']}, k={k}",
                    "B": B, "k": k, "M": M, "in_place_weights": in_place},
@@ -236,6 +281,7 @@ def main() -> int:
         "hbm_frac_whole_step": round(bytes_alg["total"] / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
         "latency_ms_vs_k": {str(kk): round(v, 4) for kk, v in curve.items()},
         "latency_ratio_vs_k0": ratio,
+        "latency_ms_vs_k_events": curve_q,
         "kernel_class_ms_per_step": classes_ms,
         "tree_step_ms": None if tree_ms is None else round(tree_ms, 4),
         "host_draft_us_per_proposal": round(draft_us, 1),

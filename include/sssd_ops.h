@@ -32,6 +32,16 @@ size_t sssd_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K,
                  float *out, void *scratch, size_t scratch_bytes, void *stream);
 
+/* Largest M = B*(k+1) that the small-step GEMM kernel (pgemm_kernel) serves; steps above it run the
+ * large-M kernel (qgemm_kernel).  For benchmarks that name the kernel a launch used. */
+int32_t sssd_op_gemm_small_step_rows(void);
+
+/* Measurement aid: one read-only pass over `bytes` (>= 16, src 16-byte aligned) of device memory by a
+ * kernel that does nothing else, i.e. the read bandwidth a kernel can reach on this device, against
+ * which the weight-streaming GEMMs (Table 2 linear rows: FLOPs:IO ~ b*s_q, so HBM-bound) are rated.
+ * sink: device uint32 [4096], receives per-workgroup XORs of the data (keeps the loads live). */
+int sssd_op_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
 /* Table 2 attention row on a context's cache: q device fp32 [B][k+1][n_q_heads][head_dim]
  * (already rotated), lens device int32 [B] (the k+1 new K/V rows of `layer` must already be
  * in the cache at lens[b]..lens[b]+k, e.g. via sssd_kv_import); row j attends to cache rows

@@ -66,6 +66,9 @@ def lib() -> C.CDLL:
         l.sssd_verify_step_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         l.sssd_kv_commit_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         l.sssd_verify_step_tree_sampled.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(SamplingParams), vp, vp, vp, vp, vp, vp]
+        l.sssd_op_gemm_small_step_rows.argtypes = []
+        l.sssd_op_gemm_small_step_rows.restype = i32
+        l.sssd_op_stream_read.argtypes = [vp, sz, vp, vp]
         l.sssd_op_sample.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
         l.sssd_kv_geometry.argtypes = [C.POINTER(ModelConfig), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
@@ -296,3 +299,14 @@ def sssd_op_sample(logits: torch.Tensor, sampling: SamplingParams, uniforms: tor
     _check(lib().sssd_op_sample(_ptr(logits), rows, vocab, C.byref(sampling), _ptr(uniforms), _ptr(out), _stream()),
            "sssd_op_sample")
     return out
+
+
+def sssd_op_gemm_small_step_rows() -> int:
+    return int(lib().sssd_op_gemm_small_step_rows())
+
+
+def sssd_op_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """One read-only pass over `src` (any dtype, contiguous); sink: int32/uint32 tensor of >= 4096 words."""
+    assert src.is_contiguous() and sink.numel() >= 4096 and sink.element_size() == 4
+    _check(lib().sssd_op_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()),
+           "sssd_op_stream_read")

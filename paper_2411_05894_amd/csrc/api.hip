@@ -710,6 +710,18 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
     return SSSD_OK;
 }
 
+int32_t sssd_op_gemm_small_step_rows(void) { return stream_gemm_max_rows(); }
+
+int sssd_op_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16 || (uintptr_t)src % 16) return SSSD_EINVAL;
+    int dev = 0, n_cu = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    HIP_TRY(launch_stream_read(src, bytes, sink, n_cu, (hipStream_t)stream));
+    return SSSD_OK;
+}
+
 int sssd_op_sample(const float *logits, int32_t rows, int32_t vocab, const sssd_sampling_params *sampling,
                    const float *uniforms, int32_t *sampled, void *stream)
 {

@@ -297,7 +297,39 @@ __global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, KvG
     }
 }
 
+// Plain read-only stream over a buffer: 16 bytes per lane and load, four loads in flight per lane,
+// grid-stride.  What it reaches is the read bandwidth a kernel on this device can get from HBM with no
+// arithmetic in the way: the yardstick the weight streamers are held against.  The XOR of everything
+// read goes to sink[workgroup] so that the loads are live.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *src, size_t n16, uint32_t *sink)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off, 64);
+    __shared__ uint32_t part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
 }  // namespace
+
+hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_cu, hipStream_t s)
+{
+    const size_t n16 = bytes / 16;
+    const int grid = n_cu * 8 < STREAM_READ_SINK_WORDS ? n_cu * 8 : STREAM_READ_SINK_WORDS;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, s, (const u32x4 *)src, n16, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val, const int *part_idx, int NT,
                          int32_t *that, hipStream_t s)

@@ -97,6 +97,10 @@ hipError_t launch_kv_copy(const Dims &D, const KvGeom &kv, uint16_t *Kc_layer, u
 // Kernel-level entry points only (parity tests, micro-benchmarks).
 hipError_t launch_pack_act(const float *X, int M, int K, uint16_t *A_hi, uint16_t *A_lo, hipStream_t s);
 hipError_t launch_unpack_act(const uint16_t *A_hi, const uint16_t *A_lo, int M, int K, float *X, hipStream_t s);
+// Read-only stream over `bytes` of device memory (the achievable-bandwidth yardstick); sink holds
+// STREAM_READ_SINK_WORDS words.
+constexpr int STREAM_READ_SINK_WORDS = 4096;
+hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_cu, hipStream_t s);
 hipError_t launch_q_pack(const Dims &D, const float *q, int B, int k, uint16_t *Qp, uint16_t *Qp_lo, hipStream_t s);
 hipError_t launch_lens(const Dims &D, int B, int k, const int32_t *lens, int32_t *pos_base, int32_t *rope_pos,
                        uint32_t *anc, int32_t *err_flag, hipStream_t s);
