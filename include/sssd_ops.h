@@ -32,6 +32,24 @@ size_t sssd_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K,
                  float *out, void *scratch, size_t scratch_bytes, void *stream);
 
+/*
+ * sssd_op_gemm for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The split-K partial sums live in
+ * a device array that is part of the library image (SSSD_OP_GEMM_STATIC_SCRATCH_BYTES, one copy per
+ * GPU, held until the process ends), so the call allocates and frees nothing, on the device or
+ * through any allocating runtime routine; its first call on a device only looks the array's address
+ * up.  Same arguments, result (bit for bit) and errors as sssd_op_gemm, except:
+ *  - SSSD_ECAPACITY when sssd_op_gemm_scratch_bytes(M, N, K) exceeds the array: the shape needs
+ *    sssd_op_gemm with a caller-provided scratch;
+ *  - all calls on one GPU share the one array: calls that overlap in time on the same GPU (different
+ *    streams, different threads) race on it and must be ordered by the caller.  Nothing in it has to
+ *    be cleared between calls: a launch only reads the partial sums it wrote itself.
+ */
+#define SSSD_OP_GEMM_STATIC_SCRATCH_BYTES (32u << 20)
+size_t sssd_op_gemm_static_scratch_limit(void);
+int sssd_op_gemm_static(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K,
+                        float *out, void *stream);
+
 /* Largest M = B*(k+1) that the small-step GEMM kernel (pgemm_kernel) serves; steps above it run the
  * large-M kernel (qgemm_kernel).  For benchmarks that name the kernel a launch used. */
 int32_t sssd_op_gemm_small_step_rows(void);

@@ -66,6 +66,9 @@ def lib() -> C.CDLL:
         l.sssd_verify_step_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         l.sssd_kv_commit_tree.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         l.sssd_verify_step_tree_sampled.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(SamplingParams), vp, vp, vp, vp, vp, vp]
+        l.sssd_op_gemm_static.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+        l.sssd_op_gemm_static_scratch_limit.argtypes = []
+        l.sssd_op_gemm_static_scratch_limit.restype = sz
         l.sssd_op_gemm_small_step_rows.argtypes = []
         l.sssd_op_gemm_small_step_rows.restype = i32
         l.sssd_op_stream_read.argtypes = [vp, sz, vp, vp]
@@ -290,6 +293,17 @@ def sssd_op_gemm(a_hi: torch.Tensor, a_lo: torch.Tensor, w_packed: torch.Tensor,
     _check(lib().sssd_op_gemm(_ptr(a_hi), _ptr(a_lo), _ptr(w_packed), M, N, K, _ptr(out), _ptr(scratch), nbytes,
                               _stream()), "sssd_op_gemm")
     return out
+
+
+def sssd_op_gemm_static(a_hi: torch.Tensor, a_lo: torch.Tensor, w_packed: torch.Tensor, M: int, N: int, K: int,
+                        out: torch.Tensor) -> None:
+    """The entry point that allocates nothing: `out` (fp32 [M][N]) is the caller's, nothing is created here."""
+    _check(lib().sssd_op_gemm_static(_ptr(a_hi), _ptr(a_lo), _ptr(w_packed), M, N, K, _ptr(out), _stream()),
+           "sssd_op_gemm_static")
+
+
+def sssd_op_gemm_static_scratch_limit() -> int:
+    return int(lib().sssd_op_gemm_static_scratch_limit())
 
 
 def sssd_op_sample(logits: torch.Tensor, sampling: SamplingParams, uniforms: torch.Tensor) -> torch.Tensor:

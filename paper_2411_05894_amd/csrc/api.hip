@@ -1,4 +1,5 @@
 // C ABI of the SSSD verify library: context, buffer map, and the per-step launch sequence.
+#include <mutex>
 #include "../../include/sssd_ops.h"
 #include "kernels.h"
 
@@ -711,6 +712,51 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
 }
 
 int32_t sssd_op_gemm_small_step_rows(void) { return stream_gemm_max_rows(); }
+
+}  // extern "C"
+
+// Split-K partial sums of sssd_op_gemm_static.  One copy per device, held until the process ends.
+// In host code the name is only a handle: static_scratch_ptr() asks the runtime for the address of
+// the CURRENT device's copy, once per device, and everything else uses that address.
+static __device__ __align__(256) unsigned char static_scratch[SSSD_OP_GEMM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex static_scratch_mu;
+void *static_scratch_addr[MAX_DEVICES];   // per device, nullptr until resolved
+
+int static_scratch_ptr(void **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return SSSD_EINVAL;
+    std::lock_guard<std::mutex> lock(static_scratch_mu);
+    if (!static_scratch_addr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+        if (!p) return SSSD_EHIP;
+        static_scratch_addr[dev] = p;
+    }
+    *out = static_scratch_addr[dev];
+    return SSSD_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sssd_op_gemm_static_scratch_limit(void) { return SSSD_OP_GEMM_STATIC_SCRATCH_BYTES; }
+
+int sssd_op_gemm_static(const void *a_hi, const void *a_lo, const void *w_packed, int32_t M, int32_t N, int32_t K,
+                        float *out, void *stream)
+{
+    if (!a_hi || !a_lo || !w_packed || !out || M <= 0 || N <= 0 || K <= 0 || N % 16) return SSSD_EINVAL;
+    if (stream_gemm_scratch_bytes(M, N, K) > (size_t)SSSD_OP_GEMM_STATIC_SCRATCH_BYTES) return SSSD_ECAPACITY;
+    void *scratch = nullptr;
+    const int rc = static_scratch_ptr(&scratch);
+    if (rc) return rc;
+    // every partial slice a launch reads was written by the same launch: nothing has to start at zero
+    return sssd_op_gemm(a_hi, a_lo, w_packed, M, N, K, out, scratch, SSSD_OP_GEMM_STATIC_SCRATCH_BYTES, stream);
+}
 
 int sssd_op_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
 {
