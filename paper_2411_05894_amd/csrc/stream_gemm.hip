@@ -41,46 +41,68 @@ namespace {
 // ------------------------------------------------------------------ M <= 32 ----
 constexpr int PW = 16;  // waves per workgroup
 
-template <int KPW, int MT, bool PREFETCH, int WN>
-__device__ __forceinline__ void stream_tile(const u32x4 (&ah)[MT][KPW], const u32x4 (&al)[MT][KPW], u32x4 (&w)[WN], const u32x4 *wn,
-                                            const int (&koff)[KPW], f32x4 (&acc)[MT])
+// Weight tile load.  One reader per byte (RH == 1): streaming, the line is not worth keeping.  Two
+// workgroups of a die reading the same tiles (RH == 2): an ordinary load, so that the line is still in
+// the die's L2 when the second request comes.
+template <int RH> __device__ __forceinline__ u32x4 wload(const u32x4 *p)
 {
-    f32x4 s0[MT], s1[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) s0[mt] = s1[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < KPW; ++i) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            s0[mt] = mfma(ah[mt][i], w[i], s0[mt]);
-            s1[mt] = mfma(al[mt][i], w[i], s1[mt]);
-        }
-        if (PREFETCH) w[i] = __builtin_nontemporal_load(wn + koff[i]);
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = s0[mt] + s1[mt];
+    return RH == 1 ? __builtin_nontemporal_load(p) : *p;
 }
 
-// grid = n_groups * J workgroups of 1024 threads; MT row tiles of 16 (M <= 16*MT).  Workgroup
+template <int KPW, bool PREFETCH, int RH>
+__device__ __forceinline__ f32x4 stream_tile(const u32x4 (&ah)[KPW], const u32x4 (&al)[KPW], u32x4 (&w)[KPW], const u32x4 *wn,
+                                             const int (&koff)[KPW])
+{
+    f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) {
+        s0 = mfma(ah[i], w[i], s0);
+        s1 = mfma(al[i], w[i], s1);
+        if (PREFETCH) w[i] = wload<RH>(wn + koff[i]);
+    }
+    return s0 + s1;
+}
+
+// grid = RH * n_groups * J workgroups of 1024 threads, each on one row tile of 16.  Workgroup
 // (grp, j) computes its units over k-tiles [j*16*KPW, (j+1)*16*KPW); with J > 1 (SPLIT) it stores
 // fp32 partial tiles, and the workgroup of a column group that arrives last sums them and applies the
 // epilogue (epi_kernel does, in a second launch, when the launcher has no arrival counters for it).
 // The unsplit instantiation carries none of that code (the QKV kernel is at the register limit).
-template <int EPI, int KPW, int MT, bool SPLIT>
+//
+// RH == 2 serves 17..32 rows without giving up the register-resident activations: the launch holds
+// every workgroup twice, once for rows 0..15 and once for rows 16..31 (row tile rt), and the two copies
+// sit 8 apart in the grid, i.e. on the same die, where they start together and ask for the same weight
+// tiles: one of the two requests is served by the die's L2 (or merged with the other in flight), so
+// HBM still sees each weight byte once (measured: 1.02 x the matrix bytes fetched per launch).
+template <int EPI, int KPW, bool SPLIT, int RH>
 __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 {
     constexpr int TPU = Unit<EPI>::TILES;
-    constexpr int NBUF = MT == 1 ? 2 : 1;   // two row tiles: one reduction buffer (32 KiB) and a second barrier
-    __shared__ float red[NBUF][PW][MT * 256];
-    __shared__ float rstd_s[MT * 16];
+    __shared__ float red[2][PW][256];
+    __shared__ float rstd_s[16];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int J = SPLIT ? a.J : 1, j = SPLIT ? blockIdx.x % J : 0, grp = SPLIT ? blockIdx.x / J : blockIdx.x;
+    // logical workgroup `bid` of `nblk`, and the row tile it serves
+    int bid = blockIdx.x, nblk = gridDim.x, rt = 0;
+    if (RH == 2) {
+        nblk >>= 1;
+        const int paired = nblk & ~7, b = blockIdx.x;           // whole sets of 8 logical workgroups, then the rest
+        if (b < 2 * paired) {
+            rt = (b >> 3) & 1;
+            bid = ((b >> 4) << 3) | (b & 7);
+        } else {
+            const int rem = nblk - paired;
+            rt = (b - 2 * paired) / rem;
+            bid = paired + (b - 2 * paired) % rem;
+        }
+    }
+    const int m_base = 16 * rt;
+    const int J = SPLIT ? a.J : 1, j = SPLIT ? bid % J : 0, grp = SPLIT ? bid / J : bid;
     const int KT = a.KT;
     const int kt0 = (j * PW + wave) * KPW;
     // Units grp, grp + groups, grp + 2*groups, ... so that at any time the workgroups of a launch
     // read neighbouring tiles (measured 3 % faster on the layer matrices); the LM head, 30 times as
     // many tiles, measured 3 % faster with a contiguous run of upw units per workgroup.
-    const int groups = gridDim.x / J;
+    const int groups = nblk / J;
     constexpr bool RUNS = EPI == FEPI_LM;
     const int u_begin = RUNS ? grp * a.upw : grp, u_stride = RUNS ? 1 : groups;
     if (u_begin >= a.n_units) return;
@@ -92,81 +114,73 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
 #pragma unroll
     for (int i = 0; i < KPW; ++i) koff[i] = (kt0 + i < KT ? kt0 + i : KT - 1) * 64;
 
-    u32x4 w[KPW], ah[MT][KPW], al[MT][KPW];
+    u32x4 w[KPW], ah[KPW], al[KPW];
     const u32x4 *wp = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin, 0)) + lane;
 #pragma unroll
-    for (int i = 0; i < KPW; ++i) w[i] = __builtin_nontemporal_load(wp + koff[i]);
+    for (int i = 0; i < KPW; ++i) w[i] = wload<RH>(wp + koff[i]);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int i = 0; i < KPW; ++i) {
-            const bool live = kt0 + i < KT;
-            const size_t at = (size_t)mt * KT * 64 + koff[i] + lane;
-            ah[mt][i] = live ? a.A_hi[at] : u32x4{0, 0, 0, 0};
-            al[mt][i] = live ? a.A_lo[at] : u32x4{0, 0, 0, 0};
-        }
-    if (EPI != FEPI_RESID && EPI != FEPI_STORE && !SPLIT) {   // published by the first barrier
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
+    for (int i = 0; i < KPW; ++i) {
+        const bool live = kt0 + i < KT;
+        const size_t at = (size_t)rt * KT * 64 + koff[i] + lane;
+        ah[i] = live ? a.A_hi[at] : u32x4{0, 0, 0, 0};
+        al[i] = live ? a.A_lo[at] : u32x4{0, 0, 0, 0};
     }
+    if (EPI != FEPI_RESID && EPI != FEPI_STORE && !SPLIT) rstd_s[wave] = row_rstd(a, m_base + wave, lane);   // published by the first barrier
 
     float keep = 0.f;
     for (int s = 0; s < n_steps; ++s) {
         const int unit = u_begin + (s / TPU) * u_stride, part = s % TPU;
-        f32x4 acc[MT];
+        f32x4 acc;
         if (s + 1 < n_steps) {
             const u32x4 *wn = tile_weights<EPI>(a, unit_tile<EPI>(a, u_begin + ((s + 1) / TPU) * u_stride, (s + 1) % TPU)) + lane;
-            stream_tile<KPW, MT, true, KPW>(ah, al, w, wn, koff, acc);
+            acc = stream_tile<KPW, true, RH>(ah, al, w, wn, koff);
         } else {
-            stream_tile<KPW, MT, false, KPW>(ah, al, w, nullptr, koff, acc);
+            acc = stream_tile<KPW, false, RH>(ah, al, w, nullptr, koff);
         }
-        float *rb = &red[NBUF == 2 ? (s & 1) : 0][0][0];
+        float *rb = &red[s & 1][0][0];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) rb[wave * (MT * 256) + mt * 256 + r * 64 + lane] = acc[mt][r];
+        for (int r = 0; r < 4; ++r) rb[wave * 256 + r * 64 + lane] = acc[r];
         __syncthreads();
-        // Two buffers: buffer s&1 is rewritten at step s+2, after the barrier of step s+1, which the
-        // reducing waves reach only after they have read it.  One buffer: the barrier below.
-        if (wave < 4 * MT) {
+        // Buffer s&1 is rewritten at step s+2, after the barrier of step s+1, which the reducing waves
+        // reach only after they have read it.
+        if (wave < 4) {
             float v = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < PW; ++ww) v += rb[ww * (MT * 256) + wave * 64 + lane];
-            const int m = 16 * (wave >> 2) + 4 * (lane >> 4) + (wave & 3), c = lane & 15;
+            for (int ww = 0; ww < PW; ++ww) v += rb[ww * 256 + wave * 64 + lane];
+            const int ml = 4 * (lane >> 4) + wave, m = m_base + ml, c = lane & 15;
             if (SPLIT) {
                 // device-scope: read back by the last workgroup of the group, on whichever die it runs
                 st<true>(a.partials + ((size_t)j * a.part_rows + m) * a.Ntot + unit_tile<EPI>(a, unit, part) * 16 + c, v);
             } else if (TPU == 2 && part == 0) {
                 keep = v;
             } else {
-                const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[m];
+                const float rs = (EPI == FEPI_RESID || EPI == FEPI_STORE) ? 1.f : rstd_s[ml];
                 if (TPU == 2) epilogue<EPI>(a, unit, m, c, m < a.M, keep, v, rs);
                 else epilogue<EPI>(a, unit, m, c, m < a.M, v, 0.f, rs);
             }
         }
-        if (NBUF == 1) __syncthreads();
     }
 
-    // Split K with arrival counters: the workgroup of a column group that finishes last sums the
-    // group's slices (in slice order, so the result does not depend on which one that is) and applies
-    // the epilogue -- no second launch.  The slices were stored device-scope and each wave waits for
-    // its stores before the workgroup is counted; they are read back device-scope.  The counter is
-    // back at zero for the next launch on the stream.
+    // Split K with arrival counters: the workgroup of a (row tile, column group) that finishes last
+    // sums the group's slices (in slice order, so the result does not depend on which one that is)
+    // and applies the epilogue -- no second launch.  The slices were stored device-scope and each wave
+    // waits for its stores before the workgroup is counted; they are read back device-scope.  The
+    // counter is back at zero for the next launch on the stream.
     if (SPLIT && a.tail_count) {
         __shared__ int last_s;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (threadIdx.x == 0) {
-            const int old = __hip_atomic_fetch_add(a.tail_count + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int *count = a.tail_count + rt * groups + grp;
+            const int old = __hip_atomic_fetch_add(count, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             last_s = old == J - 1;
-            if (old == J - 1) __hip_atomic_store(a.tail_count + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == J - 1) __hip_atomic_store(count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         if (!last_s) return;
         constexpr bool SCALED = EPI != FEPI_RESID && EPI != FEPI_STORE;
         if (SCALED) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) rstd_s[mt * 16 + wave] = row_rstd(a, mt * 16 + wave, lane);
+            rstd_s[wave] = row_rstd(a, m_base + wave, lane);
             __syncthreads();
         }
         if (EPI == FEPI_RESID) {
@@ -175,19 +189,16 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
             const int r = lane & 15, kg = lane >> 4;
             for (int i = 2 * wave + (kg >> 1); i - (kg >> 1) < n_mine; i += 2 * PW) {
                 const int unit = u_begin + i * u_stride, col = unit * 16 + (kg & 1) * 8;
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const int m = mt * 16 + r;
-                    const bool live = i < n_mine && m < a.M;
-                    Vec8 v0{};
-                    if (live) v0 = sum_slices<true>(a, m, col);
-                    resid_block<false>(a, m, col, live, kg, v0);
-                }
+                const int m = m_base + r;
+                const bool live = i < n_mine && m < a.M;
+                Vec8 v0{};
+                if (live) v0 = sum_slices<true>(a, m, col);
+                resid_block<false>(a, m, col, live, kg, v0);
             }
         } else {
             const size_t jstride = (size_t)a.part_rows * a.Ntot;
-            for (int e = threadIdx.x; e < n_mine * (MT * 256); e += PW * 64) {   // 16 adjacent lanes: one row of a unit
-                const int unit = u_begin + (e / (MT * 256)) * u_stride, m = (e % (MT * 256)) >> 4, c = e & 15;
+            for (int e = threadIdx.x; e < n_mine * 256; e += PW * 64) {   // 16 adjacent lanes: one row of a unit
+                const int unit = u_begin + (e >> 8) * u_stride, ml = (e & 255) >> 4, m = m_base + ml, c = e & 15;
                 float v[TPU];
 #pragma unroll
                 for (int part = 0; part < TPU; ++part) {
@@ -196,7 +207,7 @@ __global__ __launch_bounds__(PW * 64) void pgemm_kernel(FusedGemmArgs a)
                     for (int jj = 1; jj < J; ++jj) sum += ld<true>(pp + jj * jstride);
                     v[part] = sum;
                 }
-                epilogue<EPI>(a, unit, m, c, m < a.M, v[0], TPU == 2 ? v[TPU - 1] : 0.f, SCALED ? rstd_s[m] : 1.f);
+                epilogue<EPI>(a, unit, m, c, m < a.M, v[0], TPU == 2 ? v[TPU - 1] : 0.f, SCALED ? rstd_s[ml] : 1.f);
             }
         }
     }
@@ -641,26 +652,21 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool
     return hipSuccess;
 }
 
-// k-tiles per wave.  One row tile: 7 when K is a multiple of 16*7*32 but not of 16*8*32 (the FFN
-// widths of the Llama shapes), else 8.  Two row tiles: 4 (twice the activations per k-tile in
-// registers).  A ragged K split is legal in every case.
-__host__ int small_kpw(int KT, int mt)
-{
-    if (mt == 2) return 4;
-    return (KT % (PW * 7) == 0 && KT % (PW * 8) != 0) ? 7 : 8;
-}
+// k-tiles per wave: 7 when K is a multiple of 16*7*32 but not of 16*8*32 (the FFN widths of the
+// Llama shapes), else 8.  A ragged K split is legal in every case.
+__host__ int small_kpw(int KT) { return (KT % (PW * 7) == 0 && KT % (PW * 8) != 0) ? 7 : 8; }
 
 struct SmallPlan {
-    int mt, kpw, J, upw, groups;
+    int rh, kpw, J, upw, groups;
 };
 
 __host__ SmallPlan small_plan(const FusedGemmArgs &a)
 {
     SmallPlan p;
-    p.mt = a.M <= 16 ? 1 : 2;
-    p.kpw = small_kpw(a.KT, p.mt);
+    p.rh = a.M > 16 ? 2 : 1;   // 17..32 rows: every workgroup twice, one per row tile
+    p.kpw = small_kpw(a.KT);
     p.J = (a.KT + PW * p.kpw - 1) / (PW * p.kpw);
-    const int n_cu = a.n_cu > 0 ? a.n_cu : 256;
+    const int n_cu = (a.n_cu > 0 ? a.n_cu : 256) / p.rh;
     int groups_target = n_cu / p.J;
     if (groups_target < 1) groups_target = 1;
     p.upw = (a.n_units + groups_target - 1) / groups_target;
@@ -671,20 +677,21 @@ __host__ SmallPlan small_plan(const FusedGemmArgs &a)
 template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool *needs_epilogue, hipEvent_t t0, hipEvent_t t1)
 {
     const SmallPlan sp = small_plan(a);
-    const int mt = sp.mt, kpw = sp.kpw, groups = sp.groups;
+    const int kpw = sp.kpw, groups = sp.groups;
     a.J = sp.J;
     a.upw = sp.upw;
     a.groups = sp.groups;
-    a.part_rows = 16 * mt;
+    a.part_rows = 16 * sp.rh;
     if (a.J > 1 && (size_t)a.J * a.part_rows * a.Ntot * sizeof(float) > a.partial_bytes) return hipErrorInvalidValue;
-    const dim3 grid(groups * a.J), block(PW * 64);
-    if (groups > a.tail_slots) a.tail_count = nullptr;   // no counter for every group: epilogue launch
-#define SSSD_PLAUNCH(KPW, MT)                                                                                   \
+    const dim3 grid(groups * a.J * sp.rh), block(PW * 64);
+    if (groups * sp.rh > a.tail_slots) a.tail_count = nullptr;   // no counter for every group: epilogue launch
+#define SSSD_PLAUNCH(KPW, RH)                                                                                   \
     do {                                                                                                        \
-        if (a.J > 1) hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, MT, true>), grid, block, 0, s, t0, t1, 0, a); \
-        else hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, MT, false>), grid, block, 0, s, t0, t1, 0, a);       \
+        if (a.J > 1) hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, true, RH>), grid, block, 0, s, t0, t1, 0, a); \
+        else hipExtLaunchKernelGGL((pgemm_kernel<EPI, KPW, false, RH>), grid, block, 0, s, t0, t1, 0, a);       \
     } while (0)
-    if (mt == 2) SSSD_PLAUNCH(4, 2);
+    if (sp.rh == 2 && kpw == 7) SSSD_PLAUNCH(7, 2);
+    else if (sp.rh == 2) SSSD_PLAUNCH(8, 2);
     else if (kpw == 7) SSSD_PLAUNCH(7, 1);
     else SSSD_PLAUNCH(8, 1);
 #undef SSSD_PLAUNCH
@@ -700,18 +707,17 @@ int stream_gemm_max_rows() { return 32; }
 size_t stream_gemm_partial_bytes(const Dims &D, int M)
 {
     size_t best = 0;
-    for (int mt = 1; mt <= (M > 16 ? 2 : 1); ++mt) {
-        auto consider = [&](int K, size_t ntot) {
-            const int KT = (K + 31) / 32, ks = PW * small_kpw(KT, mt);
-            const size_t need = (size_t)((KT + ks - 1) / ks) * 16 * mt * ntot;
-            if (need > 16 * mt * ntot && need > best) best = need;   // only a split K needs scratch
-        };
-        consider(D.h, (size_t)D.qd + 2 * D.kd);
-        consider(D.qd, D.h);
-        consider(D.h, 2 * (size_t)D.f);
-        consider(D.f, D.h);
-        consider(D.h, D.V);
-    }
+    const size_t rows_small = M > 16 ? 32 : 16;
+    auto consider = [&](int K, size_t ntot) {
+        const int KT = (K + 31) / 32, ks = PW * small_kpw(KT);
+        const size_t need = (size_t)((KT + ks - 1) / ks) * rows_small * ntot;
+        if (need > rows_small * ntot && need > best) best = need;   // only a split K needs scratch
+    };
+    consider(D.h, (size_t)D.qd + 2 * D.kd);
+    consider(D.qd, D.h);
+    consider(D.h, 2 * (size_t)D.f);
+    consider(D.f, D.h);
+    consider(D.h, D.V);
     // larger steps: the K split depends on the row count's class (32-row tiles), so take the worst
     // case over every step size up to M
     for (int mc = 32; M > stream_gemm_max_rows(); mc += 32) {
@@ -735,9 +741,9 @@ size_t stream_gemm_scratch_bytes(int M, int N, int K)
 {
     const int KT = (K + 31) / 32;
     if (M > stream_gemm_max_rows()) return (size_t)q_plan(N, K, M).J * round_up(M, 16) * N * sizeof(float);
-    const int mt = M <= 16 ? 1 : 2, ks = PW * small_kpw(KT, mt);
+    const int ks = PW * small_kpw(KT);
     const size_t j = (size_t)((KT + ks - 1) / ks);
-    return j > 1 ? j * 16 * mt * N * sizeof(float) : 0;
+    return j > 1 ? j * (M <= 16 ? 16 : 32) * N * sizeof(float) : 0;
 }
 
 hipError_t launch_stream_gemm(FusedGemmArgs &a, int epilogue, hipStream_t s, bool *needs_epilogue, hipEvent_t t0,

@@ -56,6 +56,23 @@ def test_gemm_vs_oracle(N, K):
         assert (y2 - ref).abs().max().item() <= 3e-5 * scale + 1e-6, "hi+lo activations"
 
 
+@pytest.mark.parametrize("N,K", [(32768, 256), (24592, 352)])
+def test_wide_gemm_vs_oracle(N, K):
+    """Wide matrices (more column groups than compute units) through the large-M kernel: an even and an odd
+    number of k-tiles, a last column group that is only partly inside the matrix."""
+    w = normal_bf16(24, N * 3 + K, (N, K), 0.02, device=DEV)
+    wp = sv.sssd_op_pack_weight(w)
+    wc = w.cpu()
+    for M in (33, 64, 100, 160, 163):
+        say(f"wide gemm N={N} K={K} M={M}")
+        x = normal_bf16(25, M * 7 + K, (M, K), 1.0, device=DEV).float() * 1.25
+        x += 2.0 ** -10 * normal_bf16(26, M + K, (M, K), 1.0, device=DEV).float()
+        hi, lo = sv.sssd_op_pack_activation(x)
+        ref = oracle.linear(x.cpu(), wc)
+        y = sv.sssd_op_gemm(hi, lo, wp, M, N, K).cpu()
+        assert (y - ref).abs().max().item() <= 3e-5 * ref.abs().max().item() + 1e-6
+
+
 # ------------------------------------------------------------ attention ----
 @pytest.mark.parametrize("shape_name,B,k,ctxs", [
     ("tiny", 2, 4, [0, 37]), ("tiny", 1, 0, [130]), ("tiny", 3, 7, [31, 32, 95]),
