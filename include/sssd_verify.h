@@ -78,6 +78,14 @@ typedef struct {
 int sssd_verify_sizes(const sssd_model_config *cfg, size_t *kv_bytes, size_t *ws_bytes,
                       size_t *packed_weight_bytes);
 
+/* Host computation only, no device needed: SSSD_OK when every launch of a step of B sequences x k
+ * drafts fits the buffers sssd_verify_sizes asks for under cfg (row buffers, the split-K scratch each of
+ * the five GEMM launchers plans at B*(k+1) rows, the attention partial slots), SSSD_ECAPACITY when B or
+ * k exceed the configuration -- or when the sizing and a launcher's plan ever disagree, which is what
+ * the host-side self-test sweeps for.  Follows the same statement of the step as sssd_verify_step
+ * (Sec. 3.2: b sequences x s_q = k+1 positions per pass). */
+int sssd_verify_plan_check(const sssd_model_config *cfg, int32_t B, int32_t k);
+
 /*
  * Create a context.  Synchronous (it waits for its own device work):
  *  - zero-fills kv_cache (device, >= kv_bytes) -- the cache layout is private,

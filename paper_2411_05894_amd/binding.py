@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         l.sssd_strerror.restype = C.c_char_p
         l.sssd_strerror.argtypes = [C.c_int]
         l.sssd_verify_sizes.argtypes = [C.POINTER(ModelConfig), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        l.sssd_verify_plan_check.argtypes = [C.POINTER(ModelConfig), i32, i32]
         l.sssd_verify_init.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), vp, sz, vp, sz, vp, sz,
                                        C.c_uint32, C.POINTER(vp)]
         l.sssd_verify_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]

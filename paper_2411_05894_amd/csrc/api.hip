@@ -32,6 +32,7 @@ struct Buffers {
     size_t staging_bytes;
     float *partials;
     size_t partial_bytes;
+    size_t attn_slots;   // attention partial slots ([b][kv head][split]) the buffers behind part_o / part_ml hold
 };
 
 struct Sizes {
@@ -134,6 +135,7 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
         const size_t need = (size_t)B * D.nkv * attention_splits(D, B);
         if (need > slots) slots = need;
     }
+    b.attn_slots = slots;
     const size_t prow = slots * S.q_rows_pad;
     b.part_o = (float *)take(prow * D.d * 4);
     b.part_ml = (float *)take(prow * 2 * 4);
@@ -260,6 +262,31 @@ int sssd_verify_sizes(const sssd_model_config *cfg, size_t *kv_bytes, size_t *ws
     if (kv_bytes) *kv_bytes = S.kv_bytes;
     if (ws_bytes) *ws_bytes = S.ws_bytes;
     if (packed_weight_bytes) *packed_weight_bytes = S.packed_bytes;
+    return SSSD_OK;
+}
+
+int sssd_verify_plan_check(const sssd_model_config *cfg, int32_t B, int32_t k)
+{
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (B <= 0 || k < 0) return SSSD_EINVAL;
+    const Dims D = make_dims(cfg);
+    if (B > D.max_batch || k > D.max_k) return SSSD_ECAPACITY;
+    Sizes S;
+    Buffers W;
+    compute_sizes(D, S);
+    const size_t end = layout(D, S, &W, nullptr);
+    if (end != S.ws_bytes) return SSSD_ECAPACITY;
+    const int M = B * (k + 1);
+    if (M > S.m_alloc || D.g * (k + 1) > S.q_rows_pad) return SSSD_ECAPACITY;
+    // what the GEMM launchers will ask of the split-K scratch at this row count
+    const size_t ntot[5] = {(size_t)D.qd + 2 * D.kd, (size_t)D.h, 2 * (size_t)D.f, (size_t)D.h, (size_t)D.V};
+    const int kin[5] = {D.h, D.qd, D.h, D.f, D.h};
+    for (int i = 0; i < 5; ++i)
+        if (stream_gemm_scratch_bytes(M, (int)ntot[i], kin[i]) > W.partial_bytes) return SSSD_ECAPACITY;
+    // attention partial slots: [B][kv heads][splits] x q_rows_pad rows, laid out behind part_o / part_ml
+    const size_t slots = (size_t)B * D.nkv * attention_splits(D, B);
+    if (slots > W.attn_slots || attention_splits(D, B) > 64) return SSSD_ECAPACITY;
     return SSSD_OK;
 }
 
