@@ -6,6 +6,14 @@ greedy acceptance) over one batch of synthetic input that is already resident in
 HBM.  Default workload: the Llama-3-8B-shaped decoder, B = 1, KV context 2048,
 k = 8 drafts (BASELINE config 2 at the k the benchmark spec's target is stated on),
 plus the latency curve over k = 0..16.  Prints ONE JSON line.
+
+Timing: `ms_per_step` / `value` come from EXACTLY --steps steps between two device synchronisations
+(wall clock); `step_ms_events` repeats the same steps with one HIP event pair per step (median, p10,
+p90).  `roofline.achieved` is the weight bytes of one GEMM launch over the launch's own duration (HIP
+events stamped by the dispatch itself); `stream_read_gbps` / `stream_copy_gbps` are what a plain
+read-only pass and a device copy reach in the same run, and `frac_of_achievable` rates the kernel
+against the former.  `roofline.traffic` is null unless --traffic-bytes passes in what rocprofv3's
+FETCH_SIZE + WRITE_SIZE counted for this command (profiles/ holds those runs).
 """
 from __future__ import annotations
 

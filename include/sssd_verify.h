@@ -254,7 +254,9 @@ int sssd_debug_argmax(sssd_ctx *ctx, int32_t *that);
 /*
  * Copy cache rows in (e.g. a prefilled prompt) or out, enqueued on `stream`.
  * src/dst are device bf16 [n_kv_heads][n_rows][head_dim] for cache slot b of
- * `layer`, covering rows t0 .. t0+n_rows-1 (t0 + n_rows <= max_seq).
+ * `layer`, covering rows t0 .. t0+n_rows-1 (t0 + n_rows <= max_seq).  With a block
+ * table, a row whose block is mapped outside the pool is skipped (neither side is
+ * written) and raises the sticky flag of sssd_verify_sync.
  */
 int sssd_kv_import(sssd_ctx *ctx, int32_t layer, int32_t b, int32_t t0, int32_t n_rows,
                    const void *k_src, const void *v_src, void *stream);

@@ -648,7 +648,7 @@ static int kv_copy(sssd_ctx *c, int32_t layer, int32_t b, int32_t t0, int32_t n_
     if ((long)t0 + n_rows > D.max_seq) return SSSD_ECAPACITY;
     const size_t off = (size_t)layer * c->S.kv_layer_elems;
     HIP_TRY(launch_kv_copy(D, kv_geom(c), c->Kc + off, c->Vc + off, b, t0, n_rows, (uint16_t *)k_ext, (uint16_t *)v_ext, import,
-                           (hipStream_t)stream));
+                           c->W.err_flag, (hipStream_t)stream));
     return SSSD_OK;
 }
 

@@ -86,6 +86,17 @@ __device__ __forceinline__ int kv_page(const KvGeom &g, int b, int blk)
     if (page >= g.n_pages) page = g.n_pages - 1;
     return page;
 }
+// True when every block of positions [t_first, t_last] of sequence b maps to a page inside the pool:
+// what a kernel that WRITES through the table checks first (it skips the sequence otherwise).
+__device__ __forceinline__ bool kv_pages_ok(const KvGeom &g, int b, int t_first, int t_last)
+{
+    if (!g.table) return true;
+    for (int blk = t_first >> 5; blk <= (t_last >> 5); ++blk) {
+        const int page = g.table[(size_t)b * g.blocks_per_seq + blk];
+        if (page < 0 || page >= g.n_pages) return false;
+    }
+    return true;
+}
 // bf16 offset of the (page, kv head) block inside a layer's K or V pool
 __device__ __forceinline__ size_t kv_block_offset(const KvGeom &g, int page, int kvh)
 {

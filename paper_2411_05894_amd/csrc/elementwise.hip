@@ -93,6 +93,7 @@ __global__ void kv_compact_kernel(Dims D, KvGeom kv, uint16_t *Kc, uint16_t *Vc,
     const int kvh = blockIdx.x, b = blockIdx.y, l = blockIdx.z, i = threadIdx.x;
     const int len = lens[b], n = accepted_len[b];
     if (len < 0 || n < 0 || n > k || len + k + 1 > D.max_seq) return;   // flagged by kv_commit_kernel
+    if (!kv_pages_ok(kv, b, len, len + k)) return;                       // likewise: nothing moves through a bad page
     uint16_t *kc = Kc + (size_t)l * kv_layer_elems, *vc = Vc + (size_t)l * kv_layer_elems;
     int prev = 0;
     for (int s = 1; s <= n; ++s) {
@@ -107,13 +108,14 @@ __global__ void kv_compact_kernel(Dims D, KvGeom kv, uint16_t *Kc, uint16_t *Vc,
 
 // After kv_compact_kernel: lens[b] += accepted_len[b] + 1; malformed input raises the error flag
 // and leaves lens[b] alone.
-__global__ void kv_commit_kernel(Dims D, int B, int k, int32_t *lens, const int32_t *accepted_len, const int32_t *path,
+__global__ void kv_commit_kernel(Dims D, KvGeom kv, int B, int k, int32_t *lens, const int32_t *accepted_len, const int32_t *path,
                                  int32_t *err_flag)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     const int len = lens[b], n = accepted_len[b];
     bool ok = len >= 0 && n >= 0 && n <= k && len + k + 1 <= D.max_seq;
+    ok = ok && kv_pages_ok(kv, b, len, len + k);
     int prev = 0;
     for (int s = 1; ok && s <= n; ++s) {
         const int node = path[b * (k + 1) + s];
@@ -133,11 +135,17 @@ __global__ void rollback_kernel(int B, int32_t *lens, const int32_t *accepted_le
 }
 
 // grid = (n_rows, nkv), block = d.  ext layout [nkv][n_rows][d]; Kc/Vc: the layer's pools.
+// A row whose block the table sends outside the pool is skipped (nothing written on either side) and
+// raises the sticky flag.
 __global__ void kv_copy_kernel(Dims D, KvGeom kv, uint16_t *Kc, uint16_t *Vc, int b, int t0, int n_rows, uint16_t *k_ext,
-                               uint16_t *v_ext, bool import)
+                               uint16_t *v_ext, bool import, int32_t *err_flag)
 {
     (void)D;
     const int t = blockIdx.x, kvh = blockIdx.y, i = threadIdx.x;
+    if (!kv_pages_ok(kv, b, t0 + t, t0 + t)) {
+        if (i == 0 && kvh == 0) *err_flag = 1;
+        return;
+    }
     uint16_t *kc = Kc + kcache_offset(kv, b, kvh, t0 + t, i);
     uint16_t *vc = Vc + vcache_offset(kv, b, kvh, t0 + t, i);
     const size_t e = ((size_t)kvh * n_rows + t) * kv.d + i;
@@ -358,16 +366,16 @@ hipError_t launch_kv_compact(const Dims &D, const KvGeom &kv, uint16_t *Kc, uint
                        accepted_len, path);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kv_commit_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, B, k, lens, accepted_len, path, err_flag);
+    hipLaunchKernelGGL(kv_commit_kernel, dim3((B + 63) / 64), dim3(64), 0, s, D, kv, B, k, lens, accepted_len, path, err_flag);
     return hipGetLastError();
 }
 
 hipError_t launch_kv_copy(const Dims &D, const KvGeom &kv, uint16_t *Kc_layer, uint16_t *Vc_layer, int b, int t0, int n_rows,
-                          uint16_t *k_ext, uint16_t *v_ext, bool import, hipStream_t s)
+                          uint16_t *k_ext, uint16_t *v_ext, bool import, int32_t *err_flag, hipStream_t s)
 {
     if (n_rows <= 0) return hipSuccess;
     hipLaunchKernelGGL(kv_copy_kernel, dim3(n_rows, D.nkv), dim3(D.d), 0, s, D, kv, Kc_layer, Vc_layer, b, t0, n_rows, k_ext,
-                       v_ext, import);
+                       v_ext, import, err_flag);
     return hipGetLastError();
 }
 

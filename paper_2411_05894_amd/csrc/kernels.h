@@ -92,7 +92,7 @@ hipError_t launch_kv_compact(const Dims &D, const KvGeom &kv, uint16_t *Kc, uint
                              int32_t *lens, const int32_t *accepted_len, const int32_t *path, int32_t *err_flag,
                              hipStream_t s);
 hipError_t launch_kv_copy(const Dims &D, const KvGeom &kv, uint16_t *Kc_layer, uint16_t *Vc_layer, int b, int t0, int n_rows,
-                          uint16_t *k_ext, uint16_t *v_ext, bool import, hipStream_t s);
+                          uint16_t *k_ext, uint16_t *v_ext, bool import, int32_t *err_flag, hipStream_t s);
 
 // Kernel-level entry points only (parity tests, micro-benchmarks).
 hipError_t launch_pack_act(const float *X, int M, int K, uint16_t *A_hi, uint16_t *A_lo, hipStream_t s);

@@ -55,3 +55,18 @@ def test_null_handles_are_rejected():
     assert "capacity" in sv.strerror(sv.SSSD_ECAPACITY)
     assert lib.sssd_op_packed_weight_bytes(4096, 4096) == 4096 * 4096 * 2
     assert lib.sssd_op_packed_weight_bytes(256, 688) == 256 * 704 * 2
+
+
+def test_plan_check_covers_every_step_of_a_configuration_without_gpu():
+    """sssd_verify_plan_check (host only): every (B, k) inside the configuration fits the buffers
+    sssd_verify_sizes asks for; anything beyond the configuration is a capacity error."""
+    lib = sv.lib()
+    for shape, mb, mk, ms in (("tiny", 8, 31, 260), ("8b", 32, 16, 4113), ("70b", 16, 8, 2057)):
+        cfg = sv.make_config(MODEL_SHAPES[shape], mb, mk, ms)
+        for B in range(1, mb + 1):
+            for k in range(mk + 1):
+                assert lib.sssd_verify_plan_check(C.byref(cfg), B, k) == sv.SSSD_OK, (shape, B, k)
+        assert lib.sssd_verify_plan_check(C.byref(cfg), mb + 1, 0) == sv.SSSD_ECAPACITY
+        assert lib.sssd_verify_plan_check(C.byref(cfg), 1, mk + 1) == sv.SSSD_ECAPACITY
+        assert lib.sssd_verify_plan_check(C.byref(cfg), 0, 0) == sv.SSSD_EINVAL
+    assert lib.sssd_verify_plan_check(None, 1, 0) == sv.SSSD_EINVAL

@@ -139,6 +139,28 @@ def test_block_table_errors():
     p.ctx.sssd_kv_set_block_table(table.to(DEV))
     p.ctx.sssd_verify_step(t, torch.tensor([0, 0], dtype=torch.int32, device=DEV), out, out.clone())
     assert p.ctx.sssd_verify_sync() == 0
+    # import / export / tree commit through a bad entry: the row is skipped on both sides and the flag is raised
+    s_ = p.shape
+    table[1, 1] = n_pages + 3
+    p.ctx.sssd_kv_set_block_table(table.to(DEV))
+    before = p.ctx.kv_cache.clone()
+    K = torch.ones(s_.n_kv_heads, 40, s_.head_dim, dtype=torch.bfloat16, device=DEV)
+    p.ctx.sssd_kv_import(0, 1, 0, K, K)                             # rows 0..31 go to page 3, rows 32..39 nowhere
+    assert p.ctx.sssd_verify_sync() == sv.SSSD_ENOSPACE
+    out_k = torch.full_like(K, 7.0)
+    p.ctx.sssd_kv_export(0, 1, 0, out_k, torch.full_like(K, 7.0))
+    assert p.ctx.sssd_verify_sync() == sv.SSSD_ENOSPACE
+    assert torch.equal(out_k[:, :32], K[:, :32]) and bool((out_k[:, 32:] == 7.0).all())
+    pages = lambda t: t.view(2, s_.n_layers, n_pages, -1)            # [K | V][layer][page][bytes]
+    touched = (pages(p.ctx.kv_cache) != pages(before)).any(-1)
+    assert bool(touched[:, 0, 3].all()) and int(touched.sum()) == 2   # page 3 of layer 0, in K and in V, and nothing else
+    lens_d = torch.tensor([0, 30], dtype=torch.int32, device=DEV)
+    acc_d = torch.tensor([0, 1], dtype=torch.int32, device=DEV)
+    path_d = torch.tensor([[0, -1, -1], [0, 2, -1]], dtype=torch.int32, device=DEV)
+    snap = p.ctx.kv_cache.clone()
+    p.ctx.sssd_kv_commit_tree(lens_d, acc_d, path_d)                # sequence 1 would move row 32 -> 31 through the bad page
+    assert p.ctx.sssd_verify_sync() == sv.SSSD_ENOSPACE
+    assert lens_d.tolist() == [1, 30] and torch.equal(p.ctx.kv_cache, snap)
     p.ctx.sssd_kv_set_block_table(None)
     p.ctx.sssd_verify_step(t, torch.tensor([0, 0], dtype=torch.int32, device=DEV), out, out.clone())
     assert p.ctx.sssd_verify_sync() == 0
