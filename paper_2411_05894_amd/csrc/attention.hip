@@ -337,13 +337,20 @@ template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, in
 
 }  // namespace
 
-// Positions per workgroup for a step of B sequences: about 2048 workgroups over
-// (sequence, kv head, chunk), whole 32-position blocks, at most 64 chunks per sequence and at least
-// 128 positions per chunk (shorter chunks only add partial results for the merge: at B = 1, context
-// 2048 the merge takes 6.8 us with 64-position chunks, 5.6 us with 128, the partial kernel the same).
-int attention_chunk(const Dims &D, int B)
+// Positions per workgroup for a step of B sequences with `rows` query rows per kv head: enough
+// workgroups over (sequence, kv head, chunk) to fill the device for about two rounds of what it holds
+// at once -- four workgroups per compute unit with up to three waves (row tiles) each, three with four
+// waves, two with five or six, i.e. 2048 workgroups for the narrow ones and 768 / 512 for the wide
+// ones (70B shape at k = 8, five waves: 13 chunks of 160 positions per sequence -> 4 of 544, attention
+// 7.3 -> 5.3 ms per step: every chunk fewer is a partial result of g*(k+1) rows less to write and merge)
+// -- in whole 32-position blocks, at most 64 chunks per sequence and at least 128 positions per chunk
+// (shorter chunks only add partial results for the merge: at B = 1, context 2048 the merge takes 6.8 us
+// with 64-position chunks, 5.6 us with 128, the partial kernel the same).
+int attention_chunk(const Dims &D, int B, int rows)
 {
-    long chunk = ((long)D.seq_pad * B * D.nkv + 2047) / 2048;
+    const int waves = (rows + 15) / 16 < MAX_WAVES ? (rows + 15) / 16 : MAX_WAVES;
+    const long target = waves <= 3 ? 2048 : (waves == 4 ? 768 : 512);
+    long chunk = ((long)D.seq_pad * B * D.nkv + target - 1) / target;
     const long floor64 = (D.seq_pad + 63) / 64;
     if (chunk < floor64) chunk = floor64;
     chunk = (chunk + 31) / 32 * 32;
@@ -351,17 +358,19 @@ int attention_chunk(const Dims &D, int B)
     return (int)chunk;
 }
 
+// Chunks per sequence at the narrowest step (the most chunks any step of B sequences uses): what the
+// partial-result buffers are sized for.
 int attention_splits(const Dims &D, int B)
 {
-    const int chunk = attention_chunk(D, B);
+    const int chunk = attention_chunk(D, B, 1);
     return (D.seq_pad + chunk - 1) / chunk;
 }
 
 hipError_t launch_attention(const Dims &D, const AttnArgs &a_in, hipStream_t s)
 {
     AttnArgs a = a_in;
-    a.chunk = attention_chunk(D, a.B);
-    a.n_splits = attention_splits(D, a.B);
+    a.chunk = attention_chunk(D, a.B, D.g * (a.k + 1));
+    a.n_splits = (D.seq_pad + a.chunk - 1) / a.chunk;
     const int q_rows_pad = round_up(D.g * (D.max_k + 1), 16);
     hipError_t e = D.d == 128 ? launch_partial<128>(D, a, q_rows_pad, s) : launch_partial<64>(D, a, q_rows_pad, s);
     if (e != hipSuccess) return e;

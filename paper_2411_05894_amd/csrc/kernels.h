@@ -119,7 +119,8 @@ struct AttnArgs {
     int B, k;
     int chunk, n_splits;       // filled in by launch_attention: positions per workgroup, partial slots per (b, kv head)
 };
-// Positions per workgroup and chunks per sequence for a step of B sequences (sizes the partial buffers).
-int attention_chunk(const Dims &D, int B);
+// Positions per workgroup for a step of B sequences with `rows` query rows per kv head, and the most
+// chunks per sequence any such step uses (sizes the partial buffers).
+int attention_chunk(const Dims &D, int B, int rows);
 int attention_splits(const Dims &D, int B);
 hipError_t launch_attention(const Dims &D, const AttnArgs &a, hipStream_t s);
