@@ -583,22 +583,24 @@ struct QPlan {
     int qw;               // waves (32-column tiles) per workgroup
 };
 
-// Column groups and the K split.  A workgroup slot is what one compute unit can hold of this kernel
-// at once (by the registers the row count needs, for 1..5 row tiles of 32: 2, 2, 2, 1, 1 workgroups
-// of eight waves, 5, 3, 2, 2, 2 of four; one per compute unit for the small matrices below 129 rows); the split is the smallest J whose groups*J workgroups fill whole rounds of slots to at
-// least 85 % (else the best-filling one), with at least 8 k-tiles per slice and at most 16 slices.
+// Column groups and the K split.  The split is the smallest J whose groups*J workgroups fill whole
+// rounds of one workgroup per compute unit to at least 85 % (else the best-filling one), with at least
+// 8 k-tiles per slice and at most 16 slices.  More slices than that would still find room on the device at
+// up to 96 rows (two workgroups fit a compute unit there), but every slice is another fp32 copy of the
+// output to write and read back: measured on the 70B shapes at 80 rows, filling 256 slots instead of 512
+// took QKV from 52 to 43 us, down from 113 to 91 us, O from 46 to 41 us.
 __host__ QPlan q_plan(int Ntot, int K, int M)
 {
     const int NT32 = (Ntot / 16 + 1) / 2, KT = (K + 31) / 32;
     const int mt32 = M >= 160 ? 5 : (M + 31) / 32;
-    static const int resident8[6] = {0, 2, 2, 2, 1, 1}, resident4[6] = {0, 5, 3, 2, 2, 2};
+    const size_t bytes = (size_t)Ntot * (size_t)K * 2;
     QPlan p;
-    // four waves: the small matrices, and every matrix at up to 64 rows (measured at 36 and 64 rows: gate/up 59 -> 48
-    // and 64 -> 51 us, down 34 -> 32 and 37 -> 33 us; from 65 rows on eight waves win on the large matrices)
-    p.qw = ((size_t)Ntot * (size_t)K * 2 < ((size_t)64 << 20) || mt32 <= 2) ? 4 : 8;
-    // The small matrices at up to 128 rows run best with about one workgroup per compute unit: more
-    // slices only add partial-sum traffic, which there is a sizeable fraction of the weight bytes.
-    const int slots = (p.qw == 4 && mt32 <= 4) ? 256 : 256 * (p.qw == 8 ? resident8[mt32] : resident4[mt32]);
+    // Four waves (128 columns per workgroup, K split half as often): the small matrices, and every matrix but
+    // the very large ones at up to 64 rows (measured at 36 and 64 rows on the 8B shapes: gate/up 59 -> 48 and
+    // 64 -> 51 us, down 34 -> 32 and 37 -> 33 us; from 65 rows on eight waves win on the large matrices, and
+    // on the 940 MB gate/up matrix of the 70B shape they win at 48 rows already: 189 -> 153 us without a split).
+    p.qw = (bytes < ((size_t)64 << 20) || (mt32 <= 2 && bytes < ((size_t)512 << 20))) ? 4 : 8;
+    const int slots = 256;
     p.groups = (NT32 + p.qw * QNG - 1) / (p.qw * QNG);
     int jmax = KT / 8;
     if (jmax > 16) jmax = 16;

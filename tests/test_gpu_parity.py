@@ -73,6 +73,21 @@ def test_wide_gemm_vs_oracle(N, K):
         assert (y - ref).abs().max().item() <= 3e-5 * ref.abs().max().item() + 1e-6
 
 
+def test_stream_read_yardstick_reads_every_record():
+    """The read-only bandwidth yardstick of bench.py: the XOR of the per-workgroup words it leaves behind must
+    equal the XOR of every 32-bit word of the buffer's whole 16-byte records (a skipped or doubled record would
+    show), for sizes that do and do not fill the grid's last round."""
+    import numpy as np
+    for n_words in (4, 4 * 1000 + 3, 4 * (1 << 20) + 8, 4 * 2048 * 256 * 4):
+        buf = uniform_int(91, n_words, (n_words,), 0, (1 << 31) - 1, device=DEV).to(torch.int32)
+        sink = torch.zeros(4096, dtype=torch.int32, device=DEV)
+        sv.sssd_op_stream_read(buf, sink)
+        torch.cuda.synchronize()
+        got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
+        want = int(np.bitwise_xor.reduce(buf.cpu().numpy().view(np.uint32)[: n_words // 4 * 4]))
+        assert got == want, n_words
+
+
 # ------------------------------------------------------------ attention ----
 @pytest.mark.parametrize("shape_name,B,k,ctxs", [
     ("tiny", 2, 4, [0, 37]), ("tiny", 1, 0, [130]), ("tiny", 3, 7, [31, 32, 95]),
