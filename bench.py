@@ -221,7 +221,7 @@ def main() -> int:
     classes_ms = {n: round(v["ms"] / prof_steps, 4) for n, v in prof.items()}
 
     # ---- the same step over draft trees (seeded random trees of k+1 nodes) and the host drafter's cost ----
-    tree_ms = None
+    tree_ms = sampled_ms = None
     if k >= 1:
         raw = uniform_int(4, TensorId.LENS + 7, (B, k + 1), 0, 1 << 20).tolist()
         par = torch.tensor([[0] + [raw[b][i] % i for i in range(1, k + 1)] for b in range(B)], dtype=torch.int32, device=dev)
@@ -235,6 +235,19 @@ def main() -> int:
             ctx.sssd_verify_step_tree(tok, par, lens, acc, nxt, path)
         torch.cuda.synchronize()
         tree_ms = (time.perf_counter() - t) * 1e3 / n_tree
+        # ... and with target-only speculative sampling on those trees (Sec. 4.4's setting: T 0.6, top-p 0.95)
+        uni = (uniform_int(4, TensorId.LENS + 9, (B, k + 1), 0, (1 << 24) - 1, device=dev).float() / float(1 << 24)).contiguous()
+        lscratch = torch.empty(B * (k + 1), shape.vocab, dtype=torch.float32, device=dev)
+        sp = sv.SamplingParams(0.6, 0, 0.95)
+        for _ in range(3):
+            ctx.sssd_verify_step_tree_sampled(tok, par, lens, sp, uni, lscratch, acc, nxt, path)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n_tree):
+            ctx.sssd_verify_step_tree_sampled(tok, par, lens, sp, uni, lscratch, acc, nxt, path)
+        torch.cuda.synchronize()
+        sampled_ms = (time.perf_counter() - t) * 1e3 / n_tree
+        del lscratch
     from paper_2411_05894_amd import drafter as dr
     from sssd_synth import repetitive_stream
     d = dr.Drafter(n_sequences=1)
@@ -292,6 +305,7 @@ def main() -> int:
         "latency_ms_vs_k_events": curve_q,
         "kernel_class_ms_per_step": classes_ms,
         "tree_step_ms": None if tree_ms is None else round(tree_ms, 4),
+        "sampled_tree_step_ms": None if sampled_ms is None else round(sampled_ms, 4),
         "host_draft_us_per_proposal": round(draft_us, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -72,6 +72,22 @@ int sssd_op_attention(sssd_ctx *ctx, int32_t layer, int32_t B, int32_t k, const 
 int sssd_op_sample(const float *logits, int32_t rows, int32_t vocab, const sssd_sampling_params *sampling,
                    const float *uniforms, int32_t *sampled, void *stream);
 
+
+/* The same sampler with a row spread over several workgroups when there are few rows (at most half as
+ * many as the device has compute units): a step of B = 1 samples k+1 rows, and one compute unit needs
+ * 10-15 us per pass over a 128k-token row.  The workgroups of a row merge what they find (maximum,
+ * integer histogram bins, tie counts, member mass) through `scratch` and take the same decisions from the
+ * same numbers, so the tokens are exactly those of sssd_op_sample.
+ *   scratch  device, at least sssd_op_sample_scratch_bytes(rows) bytes (0: no scratch needed, may be
+ *            NULL; the call then is sssd_op_sample), any contents; SSSD_ECAPACITY if it is smaller
+ * The workgroups of a row wait for each other inside the kernel, which takes the device to itself (the
+ * grid never exceeds the compute units); the wait is bounded: a row whose workgroups could not all meet
+ * comes back as -1 instead of hanging the device.  sssd_verify_step_tree_sampled uses this form with
+ * scratch from the context's workspace and reports such a failure as SSSD_EHIP from sssd_verify_sync. */
+size_t sssd_op_sample_scratch_bytes(int32_t rows);
+int sssd_op_sample_wide(const float *logits, int32_t rows, int32_t vocab, const sssd_sampling_params *sampling,
+                        const float *uniforms, int32_t *sampled, void *scratch, size_t scratch_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -234,7 +234,9 @@ int sssd_kv_set_block_table(sssd_ctx *ctx, const int32_t *block_table);
 
 /* Wait for `stream`, then return SSSD_ENOSPACE if any step since the last call raised
  * the device flag (a sequence that does not fit its cache rows, a token id, parent or page out of
- * range) and clear it, SSSD_EHIP if the runtime reported an error, else SSSD_OK. */
+ * range) and clear it, SSSD_EHIP if the runtime reported an error or the row sampler of a sampled step
+ * could not synchronise its workgroups (another kernel held part of the device; the step's outputs
+ * are then meaningless), else SSSD_OK. */
 int sssd_verify_sync(sssd_ctx *ctx, void *stream);
 
 /* Parity aid.  logits != NULL: every following step also stores its fp32

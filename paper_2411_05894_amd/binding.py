@@ -73,6 +73,9 @@ def lib() -> C.CDLL:
         l.sssd_op_gemm_small_step_rows.argtypes = []
         l.sssd_op_gemm_small_step_rows.restype = i32
         l.sssd_op_stream_read.argtypes = [vp, sz, vp, vp]
+        l.sssd_op_sample_scratch_bytes.argtypes = [i32]
+        l.sssd_op_sample_scratch_bytes.restype = sz
+        l.sssd_op_sample_wide.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp, sz, vp]
         l.sssd_op_sample.argtypes = [vp, i32, i32, C.POINTER(SamplingParams), vp, vp, vp]
         l.sssd_verify_sync.argtypes = [vp, vp]
         l.sssd_kv_geometry.argtypes = [C.POINTER(ModelConfig), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
@@ -313,6 +316,18 @@ def sssd_op_sample(logits: torch.Tensor, sampling: SamplingParams, uniforms: tor
     out = torch.empty(rows, dtype=torch.int32, device=logits.device)
     _check(lib().sssd_op_sample(_ptr(logits), rows, vocab, C.byref(sampling), _ptr(uniforms), _ptr(out), _stream()),
            "sssd_op_sample")
+    return out
+
+
+def sssd_op_sample_wide(logits: torch.Tensor, sampling: SamplingParams, uniforms: torch.Tensor) -> torch.Tensor:
+    """sssd_op_sample with several workgroups per row when there are few rows; the scratch is allocated here."""
+    rows, vocab = logits.shape
+    assert logits.dtype == torch.float32 and uniforms.dtype == torch.float32 and uniforms.numel() == rows
+    out = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    nbytes = lib().sssd_op_sample_scratch_bytes(rows)
+    scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=logits.device)
+    _check(lib().sssd_op_sample_wide(_ptr(logits), rows, vocab, C.byref(sampling), _ptr(uniforms), _ptr(out), _ptr(scratch),
+                                     nbytes, _stream()), "sssd_op_sample_wide")
     return out
 
 

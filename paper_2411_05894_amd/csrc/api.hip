@@ -32,6 +32,8 @@ struct Buffers {
     size_t staging_bytes;
     float *partials;
     size_t partial_bytes;
+    void *sample_scratch;         // sampled steps of few rows: the row sampler's cluster scratch
+    size_t sample_scratch_bytes;
     size_t attn_slots;   // attention partial slots ([b][kv head][split]) the buffers behind part_o / part_ml hold
 };
 
@@ -151,6 +153,8 @@ size_t layout(const Dims &D, Sizes &S, Buffers *B, uint8_t *base)
     b.rope_cs = (float *)take((size_t)D.max_seq * (D.d / 2) * 2 * 4);
     b.staging_bytes = (size_t)64 << 20;
     b.staging = take(b.staging_bytes);
+    b.sample_scratch_bytes = sample_scratch_bytes(M < 128 ? M : 128, 256);   // clusters form at up to half as many rows as compute units
+    b.sample_scratch = take(b.sample_scratch_bytes);
     b.partial_bytes = stream_gemm_partial_bytes(D, M);
     b.partials = (float *)take(b.partial_bytes);
     if (B) *B = b;
@@ -544,7 +548,8 @@ int run_step(sssd_ctx *c, int32_t B, int32_t k, const int32_t *tokens, const int
         if (c->dbg_logits)
             HIP_TRY(hipMemcpyAsync(c->dbg_logits, smp->logits, (size_t)M * D.V * 4, hipMemcpyDeviceToDevice, s));
         Prof p(c, s, SSSD_PROF_ACCEPT);
-        HIP_TRY(launch_sample_rows(smp->logits, M, D.V, smp->temperature, smp->top_k, smp->top_p, smp->uniforms, W.that_dbg, s));
+        HIP_TRY(launch_sample_rows(smp->logits, M, D.V, smp->temperature, smp->top_k, smp->top_p, smp->uniforms, W.that_dbg,
+                                   W.sample_scratch, W.sample_scratch_bytes, true, c->n_cu, W.err_flag, s));
         HIP_TRY(launch_accept(D, io, nullptr, nullptr, D.V / 16, W.that_dbg, s));
     } else {
         Prof p(c, s, SSSD_PROF_ACCEPT);
@@ -633,8 +638,10 @@ int sssd_verify_sync(sssd_ctx *c, void *stream)
     HIP_TRY(hipStreamSynchronize(s));
     if (flag) {
         HIP_TRY(hipMemsetAsync(c->W.err_flag, 0, 4, s));
+        if ((flag & 2) && c->W.sample_scratch_bytes)   // the sampler's counters are left mid-count by a failed wait
+            HIP_TRY(hipMemsetAsync(c->W.sample_scratch, 0, c->W.sample_scratch_bytes, s));
         HIP_TRY(hipStreamSynchronize(s));
-        return SSSD_ENOSPACE;
+        return (flag & 2) ? SSSD_EHIP : SSSD_ENOSPACE;   // bit 1: the row sampler's workgroups could not synchronise
     }
     return SSSD_OK;
 }
@@ -802,7 +809,38 @@ int sssd_op_sample(const float *logits, int32_t rows, int32_t vocab, const sssd_
     if (!(sampling->temperature > 0.f) || sampling->top_k < 0 || !(sampling->top_p > 0.f) || sampling->top_p > 1.f)
         return SSSD_EINVAL;
     HIP_TRY(launch_sample_rows(logits, rows, vocab, sampling->temperature, sampling->top_k, sampling->top_p, uniforms, sampled,
-                               (hipStream_t)stream));
+                               nullptr, 0, false, 0, nullptr, (hipStream_t)stream));
+    return SSSD_OK;
+}
+
+static int device_cus(int *n_cu)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    return SSSD_OK;
+}
+
+size_t sssd_op_sample_scratch_bytes(int32_t rows)
+{
+    int n_cu = 0;
+    if (rows <= 0 || device_cus(&n_cu) != SSSD_OK) return 0;
+    return sample_scratch_bytes(rows, n_cu);
+}
+
+int sssd_op_sample_wide(const float *logits, int32_t rows, int32_t vocab, const sssd_sampling_params *sampling,
+                        const float *uniforms, int32_t *sampled, void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (!logits || !sampling || !uniforms || !sampled || rows <= 0 || vocab <= 0) return SSSD_EINVAL;
+    if (!(sampling->temperature > 0.f) || sampling->top_k < 0 || !(sampling->top_p > 0.f) || sampling->top_p > 1.f)
+        return SSSD_EINVAL;
+    int n_cu = 0;
+    const int rc = device_cus(&n_cu);
+    if (rc) return rc;
+    const size_t need = sample_scratch_bytes(rows, n_cu);
+    if (need && (!scratch || scratch_bytes < need)) return SSSD_ECAPACITY;
+    HIP_TRY(launch_sample_rows(logits, rows, vocab, sampling->temperature, sampling->top_k, sampling->top_p, uniforms, sampled,
+                               need ? scratch : nullptr, scratch_bytes, false, n_cu, nullptr, (hipStream_t)stream));
     return SSSD_OK;
 }
 

@@ -82,8 +82,14 @@ hipError_t launch_accept(const Dims &D, const StepIO &io, const float *part_val,
                          int32_t *that, hipStream_t s);
 // One token per row drawn from softmax(logits / temperature) restricted by top_k (0: off) and top_p
 // (1: off), with the caller's uniform number per row; sampling.hip states the exact definition.
+// With scratch (sample_scratch_bytes(rows, n_cu) bytes) and few rows, a row is spread over a cluster of
+// workgroups; *err gets bit 1 set if a cluster could not synchronise (its rows are then -1).  scratch_clean:
+// the scratch is all zero or was last used by a launch that completed without such an error (a launch leaves
+// its counters at zero); otherwise it is cleared first.
+size_t sample_scratch_bytes(int rows, int n_cu);
 hipError_t launch_sample_rows(const float *logits, int rows, int V, float temperature, int top_k, float top_p,
-                              const float *uniforms, int32_t *sampled, hipStream_t s);
+                              const float *uniforms, int32_t *sampled, void *scratch, size_t scratch_bytes, bool scratch_clean, int n_cu,
+                              int32_t *err, hipStream_t s);
 hipError_t launch_rollback(int B, int32_t *lens, const int32_t *accepted_len, const int32_t *new_lens,
                            hipStream_t s);
 // Tree commit: in every layer move the K/V rows of the accepted nodes path[b][1..n] from cache rows

@@ -29,6 +29,8 @@ def uniforms(seed, n):
 def check_rows(logits, params, u, min_checked):
     """Kernel vs oracle on every row; returns (checked, exempt)."""
     got = sv.sssd_op_sample(logits.to(DEV), params, u.to(DEV)).cpu().tolist()
+    wide = sv.sssd_op_sample_wide(logits.to(DEV), params, u.to(DEV)).cpu().tolist()
+    assert wide == got, "several workgroups per row must draw exactly the tokens of one workgroup per row"
     checked = exempt = 0
     for r in range(logits.shape[0]):
         want, margin = oracle.sample_row(logits[r], params.temperature, params.top_k, params.top_p, float(u[r]),
@@ -145,8 +147,36 @@ def test_sampled_tree_step_vs_oracle():
                 cur_node = g_path[i]
             assert int(nxt[b]) == mine[cur_node][0]
         assert all(x == -1 for x in g_path[n + 1:])
+    # the same step again: the sampler's workgroup clusters must find their counters as the first call left them
+    acc2, nxt2, path2 = torch.empty_like(acc), torch.empty_like(nxt), torch.empty_like(path)
+    for _ in range(3):
+        p.ctx.sssd_verify_step_tree_sampled(tokens.to(DEV), parents.to(DEV), lens.to(DEV), sv.SamplingParams(T, top_k, top_p),
+                                            u.to(DEV), scratch, acc2, nxt2, path2)
+        assert p.ctx.sssd_verify_sync() == 0
+        assert torch.equal(acc, acc2) and torch.equal(nxt, nxt2) and torch.equal(path, path2)
     say(f"sampled tree step: logit err {err:.2e}, accepted {ref['accepted_len'].tolist()}")
     assert int(ref["accepted_len"].sum()) >= B
+
+
+@pytest.mark.parametrize("V,rows", [(128256, 1), (128256, 9), (128256, 33), (128256, 128), (128256, 200), (4100, 5), (52, 3)])
+def test_clustered_sampler_equals_the_single_workgroup_sampler(V, rows):
+    """Row counts from one (16 workgroups per row) to more rows than compute units/2 (one each), vocabularies
+    from fewer tokens than workgroups to the full size, logits with many exact ties (values on a coarse grid)
+    and without; every parameter combination must give identical tokens from both forms, twice in a row
+    (the second call finds the first call's scratch contents)."""
+    grid = (uniform_int(71, V + rows, (rows, V), -40, 40).float() / 8.0)            # ties everywhere
+    smooth = normal_bf16(72, V + rows, (rows, V), 1.0).float() * 2.5
+    u = uniforms(73, rows)
+    for logits in (grid, smooth):
+        z = logits.to(DEV).contiguous()
+        for T, k, p in ((0.6, 0, 0.95), (0.7, 20, 0.8), (1.0, 50, 1.0), (1.0, 0, 1.0), (1.5, 3, 0.3), (0.3, 0, 0.05)):
+            sp = sv.SamplingParams(T, k, p)
+            one = sv.sssd_op_sample(z, sp, u.to(DEV)).cpu()
+            for _ in range(2):
+                many = sv.sssd_op_sample_wide(z, sp, u.to(DEV)).cpu()
+                assert torch.equal(one, many), (V, rows, T, k, p)
+            assert int(one.min()) >= 0 and int(one.max()) < V
+    say(f"clustered sampler V={V} rows={rows}: identical tokens in 12 settings")
 
 
 def test_sampling_argument_checks():
