@@ -182,6 +182,15 @@ def test_clustered_sampler_equals_the_single_workgroup_sampler(V, rows):
 def test_sampling_argument_checks():
     z = torch.zeros(2, 64, device=DEV)
     u = torch.zeros(2, device=DEV)
+    # the clustered form wants its scratch: too little of it is refused before anything is launched
+    need = sv.lib().sssd_op_sample_scratch_bytes(2)
+    assert need > 0 and sv.lib().sssd_op_sample_scratch_bytes(100000) == 0
+    small = torch.empty(16, dtype=torch.uint8, device=DEV)
+    out = torch.empty(2, dtype=torch.int32, device=DEV)
+    import ctypes as C
+    ok = sv.SamplingParams(1.0, 0, 1.0)
+    assert sv.lib().sssd_op_sample_wide(z.data_ptr(), 2, 64, C.byref(ok), u.data_ptr(), out.data_ptr(), small.data_ptr(), 16, None) == sv.SSSD_ECAPACITY
+    assert sv.lib().sssd_op_sample_wide(z.data_ptr(), 2, 64, C.byref(ok), u.data_ptr(), out.data_ptr(), None, 0, None) == sv.SSSD_ECAPACITY
     for bad in (sv.SamplingParams(0.0, 0, 1.0), sv.SamplingParams(1.0, -1, 1.0), sv.SamplingParams(1.0, 0, 0.0),
                 sv.SamplingParams(1.0, 0, 1.5)):
         with pytest.raises(sv.SssdError):
