@@ -230,6 +230,28 @@ def test_tiny_steps_across_the_row_tilings(B, k):
     p.ctx.sssd_verify_destroy()
 
 
+@pytest.mark.parametrize("B,k", [(4, 8), (8, 7), (10, 9), (16, 9), (11, 15)])
+def test_wide_ffn_and_vocabulary_take_the_unsplit_large_m_path(B, k):
+    """A one-layer model whose gate/up matrices (ffn 14336) and LM head (vocabulary 32768) are wide enough that the
+    large-M kernel does not split K (one slice of partial sums, more column groups than compute units), beside
+    narrow QKV / O / down matrices that split it many ways.  M = 36, 64, 100, 160, 176 (two row passes)."""
+    s0 = MODEL_SHAPES["tiny"]
+    s = type(s0)(**{**s0.__dict__, "n_layers": 1, "ffn": 14336, "vocab": 32768})
+    p = Pair(s, seed=7, max_batch=B, max_k=k, max_seq=96, unit_gains=False)
+    ctxs = [int(c) for c in uniform_int(19, B * 100 + k, (B,), 0, 60)]
+    for b in range(B):
+        p.prefill_random_kv(20, b, ctxs[b], oracle_slot=b)
+    lens = torch.tensor(ctxs, dtype=torch.int32)
+    tokens = uniform_int(21, B * 100 + k, (B, k + 1), 0, s.vocab - 1)
+    ref = p.oracle.verify_step(tokens, lens, return_hidden=True)
+    gpu = p.step(tokens, lens)
+    e, ex, r = compare_step(gpu, ref, tokens)
+    herr = (gpu["hidden"] - ref["hidden"]).abs().max().item() / ref["hidden"].abs().max().item()
+    say(f"wide model M={B * (k + 1)}: worst logit err {e:.2e}, hidden rel err {herr:.2e}, exempt {ex}/{r}")
+    assert herr < 5e-3
+    p.ctx.sssd_verify_destroy()
+
+
 def test_error_reporting():
     s = MODEL_SHAPES["tiny"]
     p = Pair(s, seed=1, max_batch=2, max_k=4, max_seq=64)
