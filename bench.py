@@ -4,7 +4,7 @@
 One "step" is one whole verify pass (embed -> L decoder layers -> LM head ->
 greedy acceptance) over one batch of synthetic input that is already resident in
 HBM.  Default workload: the Llama-3-8B-shaped decoder, B = 1, KV context 2048,
-k = 8 drafts (BASELINE config 2 at the k the benchmark spec's target is stated on),
+k = 8 drafts (the benchmark's second configuration, at the k its latency target is stated on),
 plus the latency curve over k = 0..16.  Prints ONE JSON line.
 
 Timing: `ms_per_step` / `value` come from EXACTLY --steps steps between two device synchronisations

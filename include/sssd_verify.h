@@ -72,7 +72,9 @@ typedef struct {
                                  the caller's matrices are then in the library's private
                                  tile order until the process frees them                  */
 
-/* Bytes the caller must provide for a configuration (host computation only).
+/* Bytes the caller must provide for a configuration (host computation only): the KV cache of Table 2's
+ * caption (2 bytes per element, b x n_kv x s_kv x d per layer for K and for V), the workspace of one pass of
+ * App. B's operations over b x s_q rows, and the reordered copy of the 2-byte weights.
  * packed_weight_bytes is what `packed` must hold when SSSD_PACK_IN_PLACE is not
  * used (0 bytes are needed with it).  Any out pointer may be NULL. */
 int sssd_verify_sizes(const sssd_model_config *cfg, size_t *kv_bytes, size_t *ws_bytes,
@@ -87,7 +89,8 @@ int sssd_verify_sizes(const sssd_model_config *cfg, size_t *kv_bytes, size_t *ws
 int sssd_verify_plan_check(const sssd_model_config *cfg, int32_t B, int32_t k);
 
 /*
- * Create a context.  Synchronous (it waits for its own device work):
+ * Create a context for the decoder of App. B / Table 2 (the operations of one layer, p = 1) with the weights
+ * given.  Synchronous (it waits for its own device work):
  *  - zero-fills kv_cache (device, >= kv_bytes) -- the cache layout is private,
  *    use sssd_kv_import / sssd_kv_export to move rows in and out;
  *  - reorders every weight matrix into the tile order the GEMM kernels stream,
@@ -130,7 +133,9 @@ int sssd_verify_step(sssd_ctx *ctx, int32_t B, int32_t k, const int32_t *tokens,
                      void *stream);
 
 /*
- * Commit or roll back, enqueued on `stream`.  lens is device int32 [B], in-out.
+ * Commit or roll back, enqueued on `stream`: after verification only the accepted drafts and the token that
+ * follows them extend a sequence (Sec. 2; Sec. 3.2), so the cache keeps accepted_len + 1 of the k + 1 rows a
+ * step appended.  lens is device int32 [B], in-out.
  *   accepted_len != NULL: lens[b] += accepted_len[b] + 1  (root + accepted drafts stay)
  *   else new_lens != NULL: lens[b]  = new_lens[b]          (arbitrary rollback / chunked prefill)
  * No cache data moves: rows at or beyond lens[b] are simply dead.

@@ -155,7 +155,7 @@ class ModelShape:
 
 
 MODEL_SHAPES: Dict[str, ModelShape] = {
-    # BASELINE configs: tiny parity model, Llama-3-8B shape, Llama-3-70B shape.
+    # The benchmark configurations: tiny parity model, Llama-3-8B shape, Llama-3-70B shape.
     "tiny": ModelShape("tiny", 2, 256, 4, 2, 64, 688, 1024, 1e-5, 10000.0),
     "8b": ModelShape("8b", 32, 4096, 32, 8, 128, 14336, 128256, 1e-5, 500000.0),
     "70b": ModelShape("70b", 80, 8192, 64, 8, 128, 28672, 128256, 1e-5, 500000.0),
