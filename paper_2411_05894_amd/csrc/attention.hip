@@ -13,8 +13,9 @@
 // 32 positions through LDS together (double buffered, the next block's loads in flight
 // during the current block's arithmetic) and every wave reads its operands from there.
 // Per block and wave:
-//   S^T = K . Q^T        (A operand = 16 cached K rows; LDS rows are padded by 16 bytes so
-//                         the 16 rows a quarter-wave reads fall into distinct banks)
+//   S^T = K . Q^T        (A operand = 16 cached K rows; LDS rows are padded by 32 bytes, the
+//                         pitch at which this 16-rows-by-4-records read of a wave measured free
+//                         of bank conflicts -- 16 bytes of padding cost 1.5x the cycles)
 //   online softmax in registers; the row statistics need only two cross-lane xors
 //   O^T += V^T . P^T     (A operand = V in its block-transposed cache order,
 //                         B operand = the lane's own probabilities)
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 3
 {
     constexpr int KS = HD / 32, DT = HD / 16;
     constexpr int CPR = HD / 8;          // 16-byte records per cached K row
-    constexpr int KROW = CPR + 1;        // LDS row pitch in records (one record of padding)
+    constexpr int KROW = CPR + 2;        // LDS row pitch in records (two records of padding)
     constexpr int NREC = 32 * CPR;       // records of a 32-position block, K and V alike
     constexpr int T = NW * 64;
     constexpr int SPT = (NREC + T - 1) / T;   // records staged per thread and operand
