@@ -339,18 +339,20 @@ template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, in
 }  // namespace
 
 // Positions per workgroup for a step of B sequences with `rows` query rows per kv head: enough
-// workgroups over (sequence, kv head, chunk) to fill the device for about two rounds of what it holds
-// at once -- four workgroups per compute unit with up to three waves (row tiles) each, three with four
-// waves, two with five or six, i.e. 2048 workgroups for the narrow ones and 768 / 512 for the wide
-// ones (70B shape at k = 8, five waves: 13 chunks of 160 positions per sequence -> 4 of 544, attention
-// 7.3 -> 5.3 ms per step: every chunk fewer is a partial result of g*(k+1) rows less to write and merge)
-// -- in whole 32-position blocks, at most 64 chunks per sequence and at least 128 positions per chunk
-// (shorter chunks only add partial results for the merge: at B = 1, context 2048 the merge takes 6.8 us
-// with 64-position chunks, 5.6 us with 128, the partial kernel the same).
+// workgroups over (sequence, kv head, chunk) to fill the device once with what it holds at a time
+// -- four workgroups per compute unit with up to three waves (row tiles) each, three with four waves,
+// two with five or six, i.e. 1024 / 768 / 512 workgroups.  Every chunk fewer is a partial result of
+// g*(k+1) rows less to write and merge: 70B shape at k = 8, five waves, 13 chunks of 160 positions
+// per sequence -> 4 of 544: attention 7.3 -> 5.3 ms per step; 8B shape, 32 ragged sequences of
+// 1024..4096 at k = 4, two waves, 2048 -> 1024 workgroups: 10.24 -> 9.76 ms per step (1536, a round and
+// a half, measured 8 % slower than either).  In whole 32-position blocks, at most 64 chunks per
+// sequence and at least 128 positions per chunk (shorter chunks only add partial results for the
+// merge: at B = 1, context 2048 the merge takes 6.8 us with 64-position chunks, 5.6 us with 128, the
+// partial kernel the same).
 int attention_chunk(const Dims &D, int B, int rows)
 {
     const int waves = (rows + 15) / 16 < MAX_WAVES ? (rows + 15) / 16 : MAX_WAVES;
-    const long target = waves <= 3 ? 2048 : (waves == 4 ? 768 : 512);
+    const long target = waves <= 3 ? 1024 : (waves == 4 ? 768 : 512);
     long chunk = ((long)D.seq_pad * B * D.nkv + target - 1) / target;
     const long floor64 = (D.seq_pad + 63) / 64;
     if (chunk < floor64) chunk = floor64;
