@@ -338,21 +338,29 @@ template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, in
 
 }  // namespace
 
-// Positions per workgroup for a step of B sequences with `rows` query rows per kv head: enough
-// workgroups over (sequence, kv head, chunk) to fill the device once with what it holds at a time
-// -- four workgroups per compute unit with up to three waves (row tiles) each, three with four waves,
-// two with five or six, i.e. 1024 / 768 / 512 workgroups.  Every chunk fewer is a partial result of
-// g*(k+1) rows less to write and merge: 70B shape at k = 8, five waves, 13 chunks of 160 positions
-// per sequence -> 4 of 544: attention 7.3 -> 5.3 ms per step; 8B shape, 32 ragged sequences of
-// 1024..4096 at k = 4, two waves, 2048 -> 1024 workgroups: 10.24 -> 9.76 ms per step (1536, a round and
-// a half, measured 8 % slower than either).  In whole 32-position blocks, at most 64 chunks per
-// sequence and at least 128 positions per chunk (shorter chunks only add partial results for the
-// merge: at B = 1, context 2048 the merge takes 6.8 us with 64-position chunks, 5.6 us with 128, the
-// partial kernel the same).
+// Positions per workgroup for a step of B sequences with `rows` query rows per kv head.  The device
+// holds four workgroups per compute unit with up to three waves (row tiles) each, three with four
+// waves, two with five or six, i.e. 1024 / 768 / 512 at once, and a launch is kept to one such round
+// at most (a round and a half measured 8 % slower than one or two).  Within that, fewer and longer
+// chunks are faster -- every chunk is a partial result of g*(k+1) rows to write and merge, and HBM
+// serves 512 concurrent streams better than 1024 -- as long as ragged batches still even out:
+//   target = max(512, 3 chunks per (sequence, kv head)), capped at the round.
+// Measured, 8B shape, ms per step at 512 / 768 / 1024 workgroups: B = 4, context 32768, k = 8 (three
+// waves) 7.47 / 7.71 / 8.23; k = 4 (two) 6.79 / 6.95 / 6.98; k = 12 (four) 7.84 / 7.95 / 8.41; B = 16,
+// context 4096, k = 8: 9.12 / 9.22 / 9.42; 32 ragged sequences of 1024..4096 at k = 4: 9.89 / 9.54 /
+// 9.59 (two chunks per sequence leave the compute units unevenly loaded).  70B shape at k = 8, five
+// waves: 13 chunks of 160 positions per sequence -> 4 of 544: attention 7.3 -> 5.3 ms per step.
+// In whole 32-position blocks, at most 64 chunks per sequence (128 measured 4 % slower per step at
+// B = 1, context 32768) and at least 128 positions per chunk (shorter chunks only add partial
+// results for the merge: at B = 1, context 2048 the merge takes 6.8 us with 64-position chunks, 5.6 us
+// with 128, the partial kernel the same).
 int attention_chunk(const Dims &D, int B, int rows)
 {
     const int waves = (rows + 15) / 16 < MAX_WAVES ? (rows + 15) / 16 : MAX_WAVES;
-    const long target = waves <= 3 ? 1024 : (waves == 4 ? 768 : 512);
+    const long round = waves <= 3 ? 1024 : (waves == 4 ? 768 : 512);
+    long target = 3L * B * D.nkv;
+    if (target < 512) target = 512;
+    if (target > round) target = round;
     long chunk = ((long)D.seq_pad * B * D.nkv + target - 1) / target;
     const long floor64 = (D.seq_pad + 63) / 64;
     if (chunk < floor64) chunk = floor64;
