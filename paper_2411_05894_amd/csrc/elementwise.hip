@@ -305,21 +305,26 @@ __global__ __launch_bounds__(512) void fused_embed_kernel(Dims D, StepIO io, KvG
     }
 }
 
-// Plain read-only stream over a buffer: 16 bytes per lane and load, four loads in flight per lane,
-// grid-stride.  What it reaches is the read bandwidth a kernel on this device can get from HBM with no
-// arithmetic in the way: the yardstick the weight streamers are held against.  The XOR of everything
-// read goes to sink[workgroup] so that the loads are live.
+// Plain read-only stream over a buffer: workgroup b reads the 16 KiB pieces b, b + grid, b + 2 grid, ...,
+// each as four 16-byte loads per lane, all in flight together.  What it reaches is the read bandwidth a
+// kernel on this device can get from HBM with no arithmetic in the way: the yardstick the weight
+// streamers are held against.  (Measured on 2 GiB: 7.0-7.3 TB/s for 512 to 4096 workgroups of this shape;
+// the same bytes fetched thread by thread at a grid-wide stride, four loads 8 MB apart per lane, reach
+// 6.0 TB/s; 256 workgroups of 1024 threads with eight loads per lane, the launch shape of the weight
+// streamers, 6.6-6.8 TB/s.)  The XOR of everything read goes to sink[workgroup] so that the loads are live.
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *src, size_t n16, uint32_t *sink)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    constexpr size_t PIECE = 1024;   // records of a 16 KiB piece
+    const size_t n_pieces = n16 / PIECE;
     u32x4 acc = u32x4{0u, 0u, 0u, 0u};
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
-        const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-        acc ^= a ^ b ^ c ^ d;
+    for (size_t c = blockIdx.x; c < n_pieces; c += gridDim.x) {
+        const u32x4 *p = src + c * PIECE + threadIdx.x;
+        const u32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 256);
+        const u32x4 cc = __builtin_nontemporal_load(p + 512), d = __builtin_nontemporal_load(p + 768);
+        acc ^= a ^ b ^ cc ^ d;
     }
-    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    for (size_t i = n_pieces * PIECE + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+        acc ^= __builtin_nontemporal_load(src + i);
     uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off, 64);
@@ -334,7 +339,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *src, size
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_cu, hipStream_t s)
 {
     const size_t n16 = bytes / 16;
-    const int grid = n_cu * 8 < STREAM_READ_SINK_WORDS ? n_cu * 8 : STREAM_READ_SINK_WORDS;
+    const int grid = n_cu * 2 < STREAM_READ_SINK_WORDS ? n_cu * 2 : STREAM_READ_SINK_WORDS;
     hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, s, (const u32x4 *)src, n16, sink);
     return hipGetLastError();
 }
