@@ -349,7 +349,10 @@ template <int HD> hipError_t launch_partial(const Dims &D, const AttnArgs &a, in
 // waves) 7.47 / 7.71 / 8.23; k = 4 (two) 6.79 / 6.95 / 6.98; k = 12 (four) 7.84 / 7.95 / 8.41; B = 16,
 // context 4096, k = 8: 9.12 / 9.22 / 9.42; 32 ragged sequences of 1024..4096 at k = 4: 9.89 / 9.54 /
 // 9.59 (two chunks per sequence leave the compute units unevenly loaded).  70B shape at k = 8, five
-// waves: 13 chunks of 160 positions per sequence -> 4 of 544: attention 7.3 -> 5.3 ms per step.
+// waves: 13 chunks of 160 positions per sequence -> 4 of 544: attention 7.3 -> 5.3 ms per step.  With five or
+// six waves and long caches, 256 workgroups beat 512 (70B shape, 16 layers, B = 8, context 8192, k = 8:
+// 8.21 against 8.55 ms; 8B shape, B = 4, context 16384, k = 23: 8.09 against 8.45; context 32768, k = 16:
+// 9.82 against 10.09), while at B = 16, context 2048 (chunks of 1030 positions) 512 stay 1 % ahead.
 // In whole 32-position blocks, at most 64 chunks per sequence (128 measured 4 % slower per step at
 // B = 1, context 32768) and at least 128 positions per chunk (shorter chunks only add partial
 // results for the merge: at B = 1, context 2048 the merge takes 6.8 us with 64-position chunks, 5.6 us
@@ -358,10 +361,13 @@ int attention_chunk(const Dims &D, int B, int rows)
 {
     const int waves = (rows + 15) / 16 < MAX_WAVES ? (rows + 15) / 16 : MAX_WAVES;
     const long round = waves <= 3 ? 1024 : (waves == 4 ? 768 : 512);
+    const long positions = (long)D.seq_pad * B * D.nkv;
     long target = 3L * B * D.nkv;
-    if (target < 512) target = 512;
+    // five or six waves: one workgroup per compute unit when that still leaves it 2048 positions or more
+    const long least = (waves >= 5 && positions >= 256L * 2048) ? 256 : 512;
+    if (target < least) target = least;
     if (target > round) target = round;
-    long chunk = ((long)D.seq_pad * B * D.nkv + target - 1) / target;
+    long chunk = (positions + target - 1) / target;
     const long floor64 = (D.seq_pad + 63) / 64;
     if (chunk < floor64) chunk = floor64;
     chunk = (chunk + 31) / 32 * 32;
