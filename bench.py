@@ -206,8 +206,7 @@ def main() -> int:
     prof = ctx.sssd_profile_read()
     ctx.sssd_profile_enable(False)
     # dominant kernel: the weight streamer (one launch per GEMM; every weight byte is read once)
-    small = M <= sv.sssd_op_gemm_small_step_rows()
-    kname, launches = ("pgemm_kernel" if small else "qgemm_kernel"), prof["gemm"]["launches"] / prof_steps
+    kname, launches = sv.sssd_op_gemm_kernel_name(M), prof["gemm"]["launches"] / prof_steps
     ms_per_launch = prof["gemm"]["ms"] / prof["gemm"]["launches"]
     bytes_per_launch = bytes_alg["weights"] / launches
     achieved = bytes_per_launch / (ms_per_launch * 1e-3) / 1e9

@@ -51,8 +51,12 @@ int sssd_op_gemm_static(const void *a_hi, const void *a_lo, const void *w_packed
                         float *out, void *stream);
 
 /* Largest M = B*(k+1) that the small-step GEMM kernel (pgemm_kernel) serves; steps above it run the
- * large-M kernel (qgemm_kernel).  For benchmarks that name the kernel a launch used. */
+ * large-M kernels (qgemm_kernel up to 48 rows, qgemm16_kernel above).  For benchmarks. */
 int32_t sssd_op_gemm_small_step_rows(void);
+
+/* Name of the weight-streaming kernel that a GEMM of M rows launches (static string; for M > 160, of its
+ * first pass of 160 rows): "pgemm_kernel", "qgemm_kernel" or "qgemm16_kernel". */
+const char *sssd_op_gemm_kernel_name(int32_t M);
 
 /* Measurement aid: one read-only pass over `bytes` (>= 16, src 16-byte aligned) of device memory by a
  * kernel that does nothing else, i.e. the read bandwidth a kernel can reach on this device, against

@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
         l.sssd_op_gemm_static_scratch_limit.restype = sz
         l.sssd_op_gemm_small_step_rows.argtypes = []
         l.sssd_op_gemm_small_step_rows.restype = i32
+        l.sssd_op_gemm_kernel_name.argtypes = [i32]
+        l.sssd_op_gemm_kernel_name.restype = C.c_char_p
         l.sssd_op_stream_read.argtypes = [vp, sz, vp, vp]
         l.sssd_op_sample_scratch_bytes.argtypes = [i32]
         l.sssd_op_sample_scratch_bytes.restype = sz
@@ -333,6 +335,10 @@ def sssd_op_sample_wide(logits: torch.Tensor, sampling: SamplingParams, uniforms
 
 def sssd_op_gemm_small_step_rows() -> int:
     return int(lib().sssd_op_gemm_small_step_rows())
+
+
+def sssd_op_gemm_kernel_name(M: int) -> str:
+    return lib().sssd_op_gemm_kernel_name(int(M)).decode()
 
 
 def sssd_op_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:

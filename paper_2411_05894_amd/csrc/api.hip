@@ -747,6 +747,8 @@ int sssd_op_gemm(const void *a_hi, const void *a_lo, const void *w_packed, int32
 
 int32_t sssd_op_gemm_small_step_rows(void) { return stream_gemm_max_rows(); }
 
+const char *sssd_op_gemm_kernel_name(int32_t M) { return stream_gemm_kernel_name(M); }
+
 }  // extern "C"
 
 // Split-K partial sums of sssd_op_gemm_static.  One copy per device, held until the process ends.

@@ -62,6 +62,7 @@ struct FusedGemmArgs {
 };
 // M <= stream_gemm_max_rows(): persistent weight streamer; NT must be the tile count of W0.
 int stream_gemm_max_rows();
+const char *stream_gemm_kernel_name(int M);   // the kernel that serves (the first pass of) a GEMM of M rows
 size_t stream_gemm_partial_bytes(const Dims &D, int M);
 size_t stream_gemm_scratch_bytes(int M, int N, int K);   // one GEMM (kernel-level entry point)
 // Launches the weight-streaming kernel and records its plan (J, part_rows, ...) in `a`; when

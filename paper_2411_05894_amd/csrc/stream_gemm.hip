@@ -12,13 +12,15 @@
 //                  are refilled for the NEXT tile right after the MFMA that consumed them: a
 //                  rolling prefetch with a constant number of bytes in flight per wave and no
 //                  bubble at tile boundaries.  The k-split is reduced through LDS in fixed order.
-//   qgemm_kernel   M > 32 rows (up to 160 per pass).  v_mfma_f32_32x32x16_bf16 tiles: each wave of a
+//   qgemm16_kernel M > 48 rows (up to 160 per pass).  v_mfma_f32_16x16x32_bf16 tiles: each wave of a
 //                  workgroup of eight (four for the small matrices) owns 32 output columns and streams
 //                  their weights HBM -> registers (rolling prefetch, every weight byte read once), while
 //                  the activation k-tiles of the workgroup's k-slice, which all its waves need, are staged
-//                  through a register ring and a two-deep LDS ring.  The 16-row operand tiles of the packed
-//                  layout are read as the halves of 32-row MFMA operands, so one weight layout serves
-//                  both kernels.  Results go to split-K partials for epi_kernel.
+//                  through a register ring and a two-deep LDS ring.  Results go to split-K partials for
+//                  epi_kernel.
+//   qgemm_kernel   33..48 rows (and the rows a pass of 160 leaves over): the same launch on
+//                  v_mfma_f32_32x32x16_bf16, the 16-row operand tiles of the packed layout read as the
+//                  halves of 32-row MFMA operands, so one weight layout serves every kernel.
 //   epi_kernel     Sums split-K partial results (when K is split over workgroups) in fixed order
 //                  and applies the epilogue.
 //
@@ -578,6 +580,120 @@ __global__ __launch_bounds__(QW * 64) void qgemm_kernel(FusedGemmArgs a, int m_b
     }
 }
 
+// The same launch with v_mfma_f32_16x16x32_bf16 on MT16 row tiles of 16: the form used from 49 rows up.  An
+// odd number of 16-row tiles spends no MFMA on a half-empty 32-row tile (144 rows: 36 instead of 40 units of MFMA
+// time per k-tile and wave, 18 instead of 20 operand reads from LDS, nine instead of ten tiles staged), and both
+// operands are the packed tiles as stored -- lane l holds (row or column l%16, k-slots 8*(l/16)..+7) of a 16 x 32
+// tile -- so a wave's weight loads are two whole 1 KiB records per k-tile.  Staging, prefetch distance and the K
+// split are those of qgemm_kernel.  Measured against it, whole steps in one session (ms): 8B shape 80 rows
+// 6.20 -> 5.93, 112 rows 6.93 -> 6.72, 144 rows 8.02 -> 7.80, 64 / 96 / 128 / 160 rows 0-1.5 % ahead; 70B shape
+// (16 layers) 80 rows 7.67 -> 7.03, 144 rows 10.79 -> 10.28, 64 / 160 rows 3 % ahead; at 36 rows the 32 x 32 form
+// stays 4 % ahead on the 8B shape (same on the 70B shape at 48), so up to 48 rows keep it.
+template <int MT16, int QW>
+__global__ __launch_bounds__(QW * 64) void qgemm16_kernel(FusedGemmArgs a, int m_base, int NT16)
+{
+    constexpr int QDW = 4;
+    constexpr int CHUNK = MT16 * 2 * 64;          // lane records of one activation k-tile (hi and lo)
+    constexpr int APT = (CHUNK + QW * 64 - 1) / (QW * 64);
+    constexpr bool AFULL = CHUNK % (QW * 64) == 0;
+    __shared__ u32x4 ring[2][CHUNK];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int J = a.J, j = blockIdx.x % J, grp = blockIdx.x / J;
+    const int KT = a.KT;
+    const int kps = a.kps;
+    const int kt_begin = j * kps, kt_end = kt_begin + kps < KT ? kt_begin + kps : KT;
+    const int n_iter = kt_end - kt_begin;
+
+    const int n32 = grp * QW + wave;
+    const u32x4 *wp[2];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+        int t16 = 2 * n32 + ct;
+        if (t16 >= NT16) t16 = NT16 - 1;          // columns past the matrix re-read the last tile, never stored
+        wp[ct] = tile_weights_seg(a, t16) + lane;
+    }
+
+    const size_t mt_base = (size_t)(m_base >> 4);
+    const u32x4 *asrc[APT];
+#pragma unroll
+    for (int i = 0; i < APT; ++i) {
+        int q = threadIdx.x + i * QW * 64;
+        if (!AFULL && q >= CHUNK) q = CHUNK - 1;  // surplus threads re-read the last record, never stored
+        const int tile = q >> 6, rec = q & 63;    // tile = mt16 * 2 + (0: hi, 1: lo)
+        const u32x4 *base = (tile & 1) ? a.A_lo : a.A_hi;
+        asrc[i] = base + ((mt_base + (tile >> 1)) * KT) * 64 + rec;
+    }
+    auto stage_load = [&](int kt, u32x4 (&v)[APT]) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) v[i] = asrc[i][(size_t)kt * 64];
+    };
+    auto stage_store = [&](int buf, const u32x4 (&v)[APT]) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i)
+            if (AFULL || threadIdx.x + i * QW * 64 < CHUNK) ring[buf][threadIdx.x + i * QW * 64] = v[i];
+    };
+
+    f32x4 acc[MT16][2];
+#pragma unroll
+    for (int i = 0; i < MT16; ++i)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) acc[i][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 w[QDW][2], apre[QDW][APT];
+    auto issue = [&](int u, int it) {   // activation chunk and weights of iteration `it` into slot u
+        const int kt = kt_begin + (it < n_iter ? it : n_iter - 1);
+        stage_load(kt, apre[u]);
+        w[u][0] = __builtin_nontemporal_load(wp[0] + (size_t)kt * 64);
+        w[u][1] = __builtin_nontemporal_load(wp[1] + (size_t)kt * 64);
+    };
+#pragma unroll
+    for (int u = 0; u < QDW; ++u) issue(u, u);
+    stage_store(0, apre[0]);
+    __syncthreads();
+
+    auto ktile = [&](int u, int it, bool refill, bool next_chunk) {
+        const u32x4 *buf = ring[it & 1] + lane;
+#pragma unroll
+        for (int i = 0; i < MT16; ++i) {
+            const u32x4 xh = buf[(2 * i) * 64], xl = buf[(2 * i + 1) * 64];
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+                acc[i][ct] = mfma(xh, w[u][ct], acc[i][ct]);
+                acc[i][ct] = mfma(xl, w[u][ct], acc[i][ct]);
+            }
+        }
+        if (refill) issue(u, it + QDW);
+        if (next_chunk) stage_store((it + 1) & 1, apre[(u + 1) % QDW]);
+        __syncthreads();
+    };
+    int it0 = 0;
+    for (; it0 + 2 * QDW <= n_iter; it0 += QDW) {
+#pragma unroll
+        for (int u = 0; u < QDW; ++u) ktile(u, it0 + u, true, true);
+    }
+    for (; it0 < n_iter; it0 += QDW) {
+#pragma unroll
+        for (int u = 0; u < QDW; ++u) {
+            const int it = it0 + u;
+            if (it < n_iter) ktile(u, it, it + QDW < n_iter, it + 1 < n_iter);
+        }
+    }
+
+    // acc[i][ct][v] of lane l: row 16i + 4*(l/16) + v, column 32*n32 + 16*ct + l%16
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+        const int col = n32 * 32 + ct * 16 + (lane & 15);
+        if (col >= a.Ntot) continue;
+#pragma unroll
+        for (int i = 0; i < MT16; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = m_base + 16 * i + 4 * (lane >> 4) + v;
+                if (row < a.part_rows) a.partials[((size_t)j * a.part_rows + row) * a.Ntot + col] = acc[i][ct][v];
+            }
+    }
+}
+
 struct QPlan {
     int groups, J, kps;   // column groups, K slices (none empty), k-tiles per slice
     int qw;               // waves (32-column tiles) per workgroup
@@ -634,19 +750,35 @@ template <int EPI> hipError_t launch_large(FusedGemmArgs &a, hipStream_t s, bool
     const dim3 grid(p.groups * a.J), block(p.qw * 64);
     for (int m_base = 0; m_base < a.M; m_base += 160) {
         const int mt32 = (a.M - m_base + 31) / 32;
+        const int mt16 = (a.M - m_base + 15) / 16;
         hipEvent_t e0 = m_base == 0 ? t0 : nullptr, e1 = m_base + 160 >= a.M ? t1 : nullptr;   // first pass starts, last pass stops
+        if (mt16 >= 4) {   // 49 rows and more: the 16 x 16 x 32 form (measured ahead at every tile count from 4 up)
+#define SSSD_Q16LAUNCH(MT)                                                                                      \
+    do {                                                                                                        \
+        if (p.qw == 8) hipExtLaunchKernelGGL((qgemm16_kernel<MT, 8>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); \
+        else hipExtLaunchKernelGGL((qgemm16_kernel<MT, 4>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16);     \
+    } while (0)
+            switch (mt16) {
+            case 4: SSSD_Q16LAUNCH(4); break;
+            case 5: SSSD_Q16LAUNCH(5); break;
+            case 6: SSSD_Q16LAUNCH(6); break;
+            case 7: SSSD_Q16LAUNCH(7); break;
+            case 8: SSSD_Q16LAUNCH(8); break;
+            case 9: SSSD_Q16LAUNCH(9); break;
+            default: SSSD_Q16LAUNCH(10); break;
+            }
+#undef SSSD_Q16LAUNCH
+            hipError_t e16 = hipGetLastError();
+            if (e16 != hipSuccess) return e16;
+            continue;
+        }
 #define SSSD_QLAUNCH(MT)                                                                                        \
     do {                                                                                                        \
         if (p.qw == 8) hipExtLaunchKernelGGL((qgemm_kernel<MT, 8>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16); \
         else hipExtLaunchKernelGGL((qgemm_kernel<MT, 4>), grid, block, 0, s, e0, e1, 0, a, m_base, NT16);       \
     } while (0)
-        switch (mt32 > 5 ? 5 : mt32) {
-        case 1: SSSD_QLAUNCH(1); break;
-        case 2: SSSD_QLAUNCH(2); break;
-        case 3: SSSD_QLAUNCH(3); break;
-        case 4: SSSD_QLAUNCH(4); break;
-        default: SSSD_QLAUNCH(5); break;
-        }
+        if (mt32 == 1) SSSD_QLAUNCH(1);   // the rows left over by a pass of 160
+        else SSSD_QLAUNCH(2);             // 33..48 rows
 #undef SSSD_QLAUNCH
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -704,6 +836,12 @@ template <int EPI> hipError_t launch_small(FusedGemmArgs &a, hipStream_t s, bool
 }  // namespace
 
 int stream_gemm_max_rows() { return 32; }
+
+const char *stream_gemm_kernel_name(int M)
+{
+    if (M <= stream_gemm_max_rows()) return "pgemm_kernel";
+    return (M < 160 ? M : 160) > 48 ? "qgemm16_kernel" : "qgemm_kernel";
+}
 
 // Split-K scratch needed for M rows: the largest J * rows * Ntot over the model's GEMMs.
 size_t stream_gemm_partial_bytes(const Dims &D, int M)
