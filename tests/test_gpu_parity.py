@@ -45,7 +45,9 @@ def test_gemm_vs_oracle(N, K):
     w = normal_bf16(21, N * 3 + K, (N, K), 0.02, device=DEV)
     wp = sv.sssd_op_pack_weight(w)
     wc = w.cpu()
-    for M in (1, 5, 17, 32, 33, 36, 48, 80, 96, 100, 128, 160, 163):
+    # 49 rows and more run the 16-row-tile form of the large-M kernel: every tile count from 4 to 10 (and a
+    # second pass over left-over rows) is in the list, beside both row classes of the 32-row form (33..48).
+    for M in (1, 5, 17, 32, 33, 36, 48, 49, 64, 80, 96, 100, 128, 144, 160, 163):
         say(f"gemm N={N} K={K} M={M}")
         x = normal_bf16(22, M * 7 + K, (M, K), 1.0, device=DEV).float() * 1.25
         x += 2.0 ** -10 * normal_bf16(23, M + K, (M, K), 1.0, device=DEV).float()     # not bf16-representable
@@ -63,7 +65,7 @@ def test_wide_gemm_vs_oracle(N, K):
     w = normal_bf16(24, N * 3 + K, (N, K), 0.02, device=DEV)
     wp = sv.sssd_op_pack_weight(w)
     wc = w.cpu()
-    for M in (33, 64, 100, 160, 163):
+    for M in (33, 64, 100, 144, 160, 163):
         say(f"wide gemm N={N} K={K} M={M}")
         x = normal_bf16(25, M * 7 + K, (M, K), 1.0, device=DEV).float() * 1.25
         x += 2.0 ** -10 * normal_bf16(26, M + K, (M, K), 1.0, device=DEV).float()
